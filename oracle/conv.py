@@ -1,0 +1,109 @@
+"""ctypes front end of ``conv_oracle.c`` -- the seven-loop fp64 convolution oracle.
+
+TEST INFRASTRUCTURE ONLY (see the header of ``conv_oracle.c``).  ``build()`` compiles the
+C file with gcc into ``oracle/_conv_oracle.so``; nothing here touches the GPU or the HIP
+library.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "conv_oracle.c")
+_LIB = os.path.join(_HERE, "_conv_oracle.so")
+_lib = None
+
+SHAPE_FIELDS = ("n", "c", "h", "w", "k", "r", "s", "stride_h", "stride_w", "pad_h", "pad_w",
+                "dil_h", "dil_w")
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [(f, ctypes.c_int32) for f in SHAPE_FIELDS]
+
+
+def build(force=False):
+    """Compile the oracle (gcc -O2 -fopenmp).  Idempotent unless ``force``."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
+           "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        lib.oracle_conv_out_shape.restype = ctypes.c_int
+        lib.oracle_conv_out_shape.argtypes = [ctypes.POINTER(Shape),
+                                              ctypes.POINTER(ctypes.c_int64),
+                                              ctypes.POINTER(ctypes.c_int64)]
+        lib.oracle_conv2d_fwd.restype = ctypes.c_int
+        lib.oracle_conv2d_fwd.argtypes = [ctypes.POINTER(Shape), ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_int]
+        lib.oracle_conv2d_sampled.restype = ctypes.c_int
+        lib.oracle_conv2d_sampled.argtypes = [ctypes.POINTER(Shape), ctypes.c_void_p,
+                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                              ctypes.c_void_p, ctypes.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def make_shape(n, c, h, w, k, r, s, stride=(1, 1), pad=(0, 0), dil=(1, 1)):
+    return Shape(n, c, h, w, k, r, s, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+
+
+def shape_from_layer(layer):
+    """``layer`` is a mapping with the 13 SHAPE_FIELDS keys (what the workload module emits)."""
+    return Shape(*[int(layer[f]) for f in SHAPE_FIELDS])
+
+
+def out_shape(shape):
+    """(P, Q) by the floor rule, or ``None`` when the descriptor is illegal."""
+    p, q = ctypes.c_int64(), ctypes.c_int64()
+    rc = _load().oracle_conv_out_shape(ctypes.byref(shape), ctypes.byref(p), ctypes.byref(q))
+    return (p.value, q.value) if rc == 0 else None
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def conv2d(shape, x, w, threads=0):
+    """Full-tensor oracle.  Returns ``(y64, dnorm, threads_used)``; y64, dnorm are float64
+    arrays of shape [N][K][P][Q]."""
+    pq = out_shape(shape)
+    if pq is None:
+        raise ValueError("illegal convolution shape")
+    x, w = _f32(x), _f32(w)
+    assert x.size == shape.n * shape.c * shape.h * shape.w, "x size does not match the shape"
+    assert w.size == shape.k * shape.c * shape.r * shape.s, "w size does not match the shape"
+    y = np.empty((shape.n, shape.k, pq[0], pq[1]), dtype=np.float64)
+    d = np.empty_like(y)
+    used = _load().oracle_conv2d_fwd(ctypes.byref(shape), x.ctypes.data, w.ctypes.data,
+                                     y.ctypes.data, None, d.ctypes.data, int(threads))
+    if used < 0:
+        raise ValueError("oracle rejected the call")
+    return y, d, used
+
+
+def conv2d_sampled(shape, x, w, flat_idx):
+    """Oracle value and normaliser of the outputs at flat offsets ``flat_idx`` into NKPQ."""
+    x, w = _f32(x), _f32(w)
+    assert x.size == shape.n * shape.c * shape.h * shape.w
+    assert w.size == shape.k * shape.c * shape.r * shape.s
+    idx = np.ascontiguousarray(flat_idx, dtype=np.int64)
+    y = np.empty(idx.shape, dtype=np.float64)
+    d = np.empty(idx.shape, dtype=np.float64)
+    rc = _load().oracle_conv2d_sampled(ctypes.byref(shape), x.ctypes.data, w.ctypes.data,
+                                       idx.ctypes.data, idx.size, y.ctypes.data, d.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle rejected the call (rc=%d)" % rc)
+    return y, d
