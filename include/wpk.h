@@ -1,0 +1,228 @@
+/*
+ * wpk.h -- C ABI of the MI355X (gfx950) forward 2-D convolution library.
+ *
+ * The operator is the one the paper's search and code generation exist to speed up
+ * (Section 2.3 "State space": problem parameters N, C_in, C_out, K_h, K_w, H, W, Stride,
+ * Padding; Section 2.2: the sample algorithm is a cross-correlation, filter(r) * in(x+r-1)),
+ * widened to separate h/w strides, explicit symmetric zero padding and dilation:
+ *
+ *   y[n,k,p,q] = sum_{c,r,s} x[n,c, p*stride_h - pad_h + r*dil_h, q*stride_w - pad_w + s*dil_w]
+ *                            * w[k,c,r,s]            (taps outside the image count as zero)
+ *   P = floor((H + 2*pad_h - dil_h*(R-1) - 1)/stride_h) + 1,  Q alike.
+ *
+ * Conventions for every entry point
+ *   - x, w, y are DEVICE pointers owned by the caller: dense fp32, x = [N][C][H][W],
+ *     w = [K][C][R][S], y = [N][K][P][Q], at least 4-byte aligned.  y is overwritten in full
+ *     (no accumulate, no bias).  x and y must not overlap.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued
+ *     on it and the call returns without synchronising, unless stated otherwise.
+ *   - Descriptors and config structs are HOST memory, copied by value during the call.
+ *   - Return value: 0 (WPK_OK) or a negative WPK_E_* code; functions that return an id return
+ *     it as a non-negative int.  Nothing throws or aborts across this boundary.
+ *   - Calls that share a stream are ordered; calls on different streams that use the one-shot
+ *     entry points share library scratch (packed weights, lookup tables) and must not overlap.
+ *     Plans own their scratch and may run concurrently with each other.
+ *   - The library never falls back to the CPU: without a usable GPU every compute entry point
+ *     returns WPK_E_HIP.
+ */
+#ifndef WPK_H
+#define WPK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes --------------------------------------------------------------------- */
+enum {
+    WPK_OK            = 0,
+    WPK_E_BAD_DESC    = -1, /* non-positive size/stride/dilation, negative pad, P<=0 or Q<=0      */
+    WPK_E_NULL_PTR    = -2, /* a required pointer argument is NULL                                */
+    WPK_E_UNSUPPORTED = -3, /* dtype/layout other than fp32/NCHW, or a tensor beyond 2^30 elements */
+    WPK_E_HIP         = -4, /* a HIP runtime call failed; wpk_last_hip_error() has the code       */
+    WPK_E_NO_CONFIG   = -5, /* config id out of range, or not legal for this descriptor           */
+    WPK_E_BAD_ARG     = -6, /* any other invalid argument (index out of range, bad sizes ...)     */
+    WPK_E_IO          = -7, /* cache file could not be read or written                            */
+    WPK_E_VERIFY      = -8  /* tuner: no candidate reproduced the reference kernel's output       */
+};
+
+enum { WPK_F32 = 0 };
+enum { WPK_NCHW = 0 };
+
+/* ---- the convolution problem (Section 2.3 "State space", first nine observation entries) -- */
+typedef struct wpk_conv_desc {
+    int32_t n, c, h, w;             /* input batch, channels C_in, height, width                  */
+    int32_t k, r, s;                /* output channels C_out, filter rows K_h, filter columns K_w */
+    int32_t stride_h, stride_w;     /* >= 1                                                       */
+    int32_t pad_h, pad_w;           /* >= 0, zeros added on both sides (VALID = 0)                */
+    int32_t dil_h, dil_w;           /* >= 1                                                       */
+    int32_t dtype;                  /* WPK_F32                                                    */
+    int32_t layout;                 /* WPK_NCHW                                                   */
+} wpk_conv_desc;
+
+/* Validate `d` and return the output extent.  p, q may be NULL.  Host only. */
+int wpk_conv_out_shape(const wpk_conv_desc *d, int32_t *p, int32_t *q);
+
+/* 2*N*K*P*Q*C*R*S, the direct-convolution operation count, or 0 for an invalid descriptor. */
+double wpk_conv_flops(const wpk_conv_desc *d);
+
+/* Text of a status code (static storage). */
+const char *wpk_status_string(int status);
+
+/* hipError_t value of the most recent WPK_E_HIP on this thread (0 if none). */
+int wpk_last_hip_error(void);
+
+/* ---- the kernel family: one "configuration" = one chromosome (Section 2.3 "Search space") -- */
+/*
+ * Every gene is an integer with a finite range.  A chromosome is legal for a descriptor when
+ * wpk_config_legal() says so (the constraint check of Step1): the tile combination must be one
+ * the library was built with, its LDS and workgroup size must fit a gfx950 compute unit, and
+ * split_k may not exceed the number of reduction steps.
+ */
+#define WPK_N_GENES 7
+typedef struct wpk_conv_config {
+    int32_t bm;        /* output pixels per workgroup tile:      32, 64, 128, 256                    */
+    int32_t bn;        /* output channels per workgroup tile:    32, 64, 128                        */
+    int32_t bk;        /* reduction (c,r,s) entries per step:    8, 16, 32                          */
+    int32_t wm;        /* waves along the pixel dimension:       1, 2, 4                            */
+    int32_t wn;        /* waves along the channel dimension:     1, 2, 4                            */
+    int32_t split_k;   /* slices of the reduction done by separate workgroups: 1 .. 16             */
+    int32_t xcd_remap; /* 0: tiles in launch order; 1: contiguous tile ranges per XCD              */
+} wpk_conv_config;
+
+/* Gene ranges as index ranges into the value lists above: lo[g] = 0, hi[g] = count-1.
+ * wpk_config_from_genes turns gene indices into a config.  Host only. */
+int wpk_config_gene_ranges(int32_t lo[WPK_N_GENES], int32_t hi[WPK_N_GENES]);
+int wpk_config_from_genes(const int32_t genes[WPK_N_GENES], wpk_conv_config *out);
+int wpk_config_to_genes(const wpk_conv_config *cfg, int32_t genes[WPK_N_GENES]);
+
+/* Constraint check: 1 legal, 0 illegal, <0 error (bad descriptor).  Host only. */
+int wpk_config_legal(const wpk_conv_desc *d, const wpk_conv_config *cfg);
+
+/* Config ids: a dense non-negative encoding of the gene indices. */
+int wpk_config_id(const wpk_conv_config *cfg);                 /* <0 if a value is not in its list */
+int wpk_config_from_id(int id, wpk_conv_config *out);
+
+/* The library's untuned default for a descriptor (a shape heuristic).  Always legal. */
+int wpk_config_default(const wpk_conv_desc *d, wpk_conv_config *out);
+
+/* ---- one-shot convolution ------------------------------------------------------------------ */
+/*
+ * y = conv(x, w) with the cached tuned config of `d` if wpk_conv_tune()/wpk_cache_load() stored
+ * one, else the default.  w is in KCRS order and is re-packed into library scratch on every call
+ * (weights may have changed); callers with fixed weights should use a plan.
+ */
+int wpk_conv2d_fwd(const wpk_conv_desc *d, const float *x, const float *w, float *y, void *stream);
+
+/* Same with an explicit configuration (WPK_E_NO_CONFIG if illegal for d). */
+int wpk_conv2d_fwd_config(const wpk_conv_desc *d, const wpk_conv_config *cfg, const float *x,
+                          const float *w, float *y, void *stream);
+
+/* Plain one-output-per-lane direct kernel (no MFMA, no LDS, 64-bit indexing).  The on-device
+ * reference the tuner vets candidates against; also serves shapes the tiled family rejects. */
+int wpk_conv2d_ref(const wpk_conv_desc *d, const float *x, const float *w, float *y, void *stream);
+
+/* ---- tuning (Section 2.3 "Genetic search", Steps 1-4; cache: Section 3.3) --------------------- */
+typedef struct wpk_tune_options {
+    int32_t population;   /* |a|, default 24                                                     */
+    int32_t elites;       /* k, default 4                                                        */
+    int32_t next_population; /* |a'|, default = population                                        */
+    int32_t participants; /* m, default = population                                              */
+    int32_t max_generations; /* default 12                                                       */
+    int32_t patience;     /* stop after this many generations without a better best, default 4   */
+    double  mutation;     /* per-gene mutation probability, default 0.15                         */
+    double  eps;          /* Step4: all runtimes within eps of the fastest, default 0.03         */
+    uint64_t seed;        /* default 2008                                                        */
+    int32_t reps;         /* timed groups per candidate (median taken), default 5                */
+    double  min_group_us; /* each timed group is sized to last at least this long, default 200   */
+    int32_t mode;         /* 0 genetic search, 1 random search (same budget), 2 exhaustive        */
+    int32_t verbose;      /* 1: print one line per generation to stderr                          */
+} wpk_tune_options;
+
+/* Fill `o` with the defaults above. */
+void wpk_tune_default_options(wpk_tune_options *o);
+
+typedef struct wpk_tune_report {
+    wpk_conv_config best;
+    double best_us;        /* median runtime of the winner, microseconds                         */
+    double default_us;     /* runtime of wpk_config_default() under the same protocol            */
+    int32_t evaluations;   /* distinct chromosomes timed                                         */
+    int32_t generations;
+    int32_t rejected;      /* candidates that failed verification against wpk_conv2d_ref        */
+    double seconds;        /* wall time of the search                                            */
+} wpk_tune_report;
+
+/*
+ * Search the kernel family for `d` on the current device with synthetic operands the library
+ * allocates itself, verify the winner against wpk_conv2d_ref, store it in the in-memory cache and
+ * return its config id (>= 0).  A cached descriptor returns at once.  Synchronises the device.
+ */
+int wpk_conv_tune(const wpk_conv_desc *d);
+
+/* Same with options and a report (either may be NULL); `force` != 0 ignores a cached entry. */
+int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt, int force,
+                     wpk_tune_report *report);
+
+/* Cache of search results, keyed by every descriptor field ("computationally identical"
+ * operators, Section 3.1) plus the device name.  Text file, one line per entry. */
+int wpk_cache_lookup(const wpk_conv_desc *d, wpk_conv_config *out); /* 1 hit, 0 miss          */
+int wpk_cache_store(const wpk_conv_desc *d, const wpk_conv_config *cfg, double us);
+int wpk_cache_clear(void);
+int wpk_cache_size(void);
+int wpk_cache_save(const char *path);
+int wpk_cache_load(const char *path);                              /* returns entries read or <0 */
+
+/*
+ * The search engine by itself, over any integer gene space, with caller-supplied constraint and
+ * fitness callbacks (host function pointers; `user` is passed through).  Fitness: larger is
+ * better, 0 = cannot run.  Random numbers: one splitmix64 stream seeded with opt->seed, consumed
+ * in the order of Steps 1-4.  `history_pop` (generations x max(population,next_population) x
+ * n_genes, int32) and `history_fit` (generations x max(...), double), if not NULL, receive every
+ * generation (unused slots -1 / -1.0); `history_sizes` receives each generation's population size.
+ * Returns the number of generations run (>= 1) or a negative status.  Host only, no GPU needed.
+ */
+typedef int (*wpk_ga_constraint_fn)(const int32_t *genes, int32_t n_genes, void *user);
+typedef double (*wpk_ga_fitness_fn)(const int32_t *genes, int32_t n_genes, void *user);
+int wpk_ga_search(int32_t n_genes, const int32_t *lo, const int32_t *hi,
+                  wpk_ga_constraint_fn constraint, wpk_ga_fitness_fn fitness, void *user,
+                  const wpk_tune_options *opt, int32_t *best_genes, double *best_fitness,
+                  int32_t *evaluations, int32_t *history_pop, double *history_fit,
+                  int32_t *history_sizes, int32_t history_capacity);
+
+/* ---- plans: a list of layers with per-layer tuned configs and pre-packed weights ------------- */
+typedef struct wpk_plan wpk_plan;
+
+/* Build a plan for n_layers descriptors (host array).  Layers with identical descriptors share
+ * one search.  `tune` = 0 uses cached/default configs, 1 runs wpk_conv_tune on cache misses.
+ * Allocates device memory for packed weights and split-K needs; synchronises the device. */
+int wpk_conv_plan(const wpk_conv_desc *layers, int32_t n_layers, int32_t tune, wpk_plan **out);
+
+/* Copy and re-pack layer `layer`'s weights (device pointer, KCRS) into the plan, on `stream`. */
+int wpk_plan_set_weights(wpk_plan *plan, int32_t layer, const float *w, void *stream);
+
+/* Run every layer in order on `stream`: y[i] = conv(x[i], weights of layer i).  x and y are HOST
+ * arrays of n_layers DEVICE pointers.  Weights of every layer must have been set. */
+int wpk_plan_run(wpk_plan *plan, const float *const *x, float *const *y, void *stream);
+
+/* Run one layer of the plan. */
+int wpk_plan_run_layer(wpk_plan *plan, int32_t layer, const float *x, float *y, void *stream);
+
+int wpk_plan_num_layers(const wpk_plan *plan);
+int wpk_plan_num_unique(const wpk_plan *plan);                       /* distinct descriptors     */
+int wpk_plan_layer_config(const wpk_plan *plan, int32_t layer, wpk_conv_config *out);
+int wpk_plan_set_layer_config(wpk_plan *plan, int32_t layer, const wpk_conv_config *cfg);
+void wpk_plan_destroy(wpk_plan *plan);
+
+/* ---- introspection used by the benchmark ----------------------------------------------------- */
+/* Name of the device kernel a config launches (static storage), e.g. "wpk_igemm_128x64x16_2x2". */
+const char *wpk_config_kernel_name(const wpk_conv_config *cfg);
+/* Device name and compute-unit count of the current device. */
+int wpk_device_info(char *name, int32_t name_capacity, int32_t *compute_units);
+/* Library version string. */
+const char *wpk_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WPK_H */

@@ -1,0 +1,73 @@
+"""Build libwpk.so (HIP, gfx950 only) in-tree with hipcc.
+
+``python -m paper_2008_04567_amd.build`` or ``build_library()``.  Translation units are compiled
+in parallel: the host part, the API/dispatch part and eight instantiation parts of the tiled
+kernel family.  Works without a GPU (hipcc cross-compiles).
+"""
+import concurrent.futures
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+INCLUDE = os.path.join(os.path.dirname(HERE), "include")
+OBJ = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libwpk.so")
+N_PARTS = 8
+
+COMMON = ["-O3", "-fPIC", "-std=c++17", "-I" + INCLUDE, "-I" + CSRC, "-Wall", "-Wno-unused-function"]
+# packed-FP32 instructions are switched off for all device code
+DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def _hipcc():
+    for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
+        if cand and (os.path.isabs(cand) and os.path.exists(cand) or not os.path.isabs(cand)):
+            return cand
+    return "hipcc"
+
+
+def _run(cmd):
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+    if res.returncode != 0:
+        raise RuntimeError("build step failed: %s\n%s" % (" ".join(cmd), out))
+    return out
+
+
+def sources_newer_than_lib():
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    files = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(INCLUDE, "wpk.h")]
+    return any(os.path.getmtime(f) > t for f in files)
+
+
+def build_library(force=True, verbose=False):
+    """Compile and link libwpk.so.  Returns its path."""
+    if not force and not sources_newer_than_lib():
+        return LIB
+    os.makedirs(OBJ, exist_ok=True)
+    hipcc = _hipcc()
+    jobs = []
+    jobs.append([hipcc] + COMMON + ["-c", os.path.join(CSRC, "wpk_host.cpp"),
+                                    "-o", os.path.join(OBJ, "wpk_host.o")])
+    jobs.append([hipcc] + COMMON + DEVICE + ["-c", os.path.join(CSRC, "wpk_api.hip"),
+                                             "-o", os.path.join(OBJ, "wpk_api.o")])
+    for part in range(N_PARTS):
+        jobs.append([hipcc] + COMMON + DEVICE + ["-DWPK_PART=%d" % part, "-c",
+                                                 os.path.join(CSRC, "wpk_igemm_inst.hip"),
+                                                 "-o", os.path.join(OBJ, "wpk_igemm_%d.o" % part)])
+    workers = min(len(jobs), max(1, (os.cpu_count() or 4)), 16)
+    with concurrent.futures.ThreadPoolExecutor(workers) as ex:
+        for out in ex.map(_run, jobs):
+            if verbose and out.strip():
+                print(out)
+    objs = [j[-1] for j in jobs]
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build_library(force=True, verbose="-v" in sys.argv))

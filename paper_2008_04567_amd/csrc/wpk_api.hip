@@ -1,0 +1,731 @@
+// Device-facing part of libwpk: helper kernels (weight re-pack, direct reference kernel, fills,
+// comparison), kernel-family dispatch, the one-shot entry points, the on-device tuner and plans.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <chrono>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "wpk_igemm.h"
+
+namespace wpk {
+
+#define WPK_HIP(call)                                  \
+    do {                                               \
+        hipError_t e_ = (call);                        \
+        if (e_ != hipSuccess) {                        \
+            set_last_hip_error((int)e_);               \
+            return WPK_E_HIP;                          \
+        }                                              \
+    } while (0)
+
+// ---- dispatch table, same order as kVariants ------------------------------------------------------
+typedef hipError_t (*LaunchFn)(const IgemmArgs &, hipStream_t);
+#define WPK_VARIANT(PART, BM, BN, BK, WM, WN) \
+    extern template hipError_t launch_igemm<BM, BN, BK, WM, WN>(const IgemmArgs &, hipStream_t);
+#include "wpk_variants.def"
+#undef WPK_VARIANT
+#define WPK_VARIANT(PART, BM, BN, BK, WM, WN) &launch_igemm<BM, BN, BK, WM, WN>,
+static const LaunchFn kLaunch[] = {
+#include "wpk_variants.def"
+};
+#undef WPK_VARIANT
+
+// ---- helper kernels ---------------------------------------------------------------------------------
+// w[K][CRS] -> wp[CRSpad][Kpad], zero padded, through a 32x32 LDS tile so both sides coalesce.
+__global__ void __launch_bounds__(256) pack_weights_kernel(const float *__restrict__ w,
+                                                           float *__restrict__ wp, int K, int CRS,
+                                                           int Kpad)
+{
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int kk0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int k = k0 + ty + i * 8, kk = kk0 + tx;
+        tile[ty + i * 8][tx] = (k < K && kk < CRS) ? w[(size_t)k * CRS + kk] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int kk = kk0 + ty + i * 8, k = k0 + tx;
+        wp[(size_t)kk * Kpad + k] = tile[tx][ty + i * 8];
+    }
+}
+
+// One output element per lane, the three reduction loops written out; 64-bit indexing.
+__global__ void __launch_bounds__(256) direct_conv_kernel(const float *__restrict__ x,
+                                                          const float *__restrict__ w,
+                                                          float *__restrict__ y,
+                                                          float *__restrict__ dnorm,
+                                                          wpk_conv_desc d, int P, int Q, long long total)
+{
+    for (long long o = (long long)blockIdx.x * blockDim.x + threadIdx.x; o < total;
+         o += (long long)gridDim.x * blockDim.x) {
+        int q = (int)(o % Q);
+        long long t = o / Q;
+        int p = (int)(t % P);
+        t /= P;
+        int k = (int)(t % d.k);
+        long long n = t / d.k;
+        float acc = 0.0f, mag = 0.0f;
+        for (int c = 0; c < d.c; ++c)
+            for (int r = 0; r < d.r; ++r) {
+                int ih = p * d.stride_h - d.pad_h + r * d.dil_h;
+                if (ih < 0 || ih >= d.h) continue;
+                for (int s = 0; s < d.s; ++s) {
+                    int iw = q * d.stride_w - d.pad_w + s * d.dil_w;
+                    if (iw < 0 || iw >= d.w) continue;
+                    float xv = x[((n * d.c + c) * d.h + ih) * (long long)d.w + iw];
+                    float wv = w[(((long long)k * d.c + c) * d.r + r) * d.s + s];
+                    acc = fmaf(xv, wv, acc);
+                    mag += fabsf(xv * wv);
+                }
+            }
+        y[o] = acc;
+        if (dnorm) dnorm[o] = mag;
+    }
+}
+
+__global__ void fill_zero_kernel(float4 *__restrict__ p4, float *__restrict__ tail, long long n4,
+                                 int ntail)
+{
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long j = i; j < n4; j += stride) p4[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < ntail) tail[i] = 0.0f;
+}
+
+// Synthetic operands for the tuner: value = lo + (hi-lo) * hash(index, seed) / 2^24.
+__global__ void fill_hash_kernel(float *__restrict__ p, long long n, unsigned seed, float lo, float hi)
+{
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (long long)gridDim.x * blockDim.x) {
+        unsigned h = (unsigned)i * 2654435761u ^ seed;
+        h ^= h >> 16; h *= 0x7feb352du; h ^= h >> 15; h *= 0x846ca68bu; h ^= h >> 16;
+        p[i] = lo + (hi - lo) * (float)(h >> 8) * (1.0f / 16777216.0f);
+    }
+}
+
+// max over outputs of |y - ref| / max(dnorm, tiny); NaN counts as +inf.  Result as float bits.
+__global__ void compare_kernel(const float *__restrict__ y, const float *__restrict__ ref,
+                               const float *__restrict__ dnorm, long long n, unsigned *out_bits)
+{
+    float worst = 0.0f;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (long long)gridDim.x * blockDim.x) {
+        float e = fabsf(y[i] - ref[i]) / fmaxf(dnorm[i], 1e-30f);
+        if (!(e == e)) e = INFINITY;
+        worst = fmaxf(worst, e);
+    }
+    atomicMax(out_bits, __float_as_uint(worst));
+}
+
+// ---- device state -----------------------------------------------------------------------------------
+static std::mutex g_mu;
+static bool g_dev_ready = false;
+static int g_cus = 0;
+
+static int ensure_device()
+{
+    if (g_dev_ready) return WPK_OK;
+    int dev = 0;
+    WPK_HIP(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    WPK_HIP(hipGetDeviceProperties(&prop, dev));
+    g_cus = prop.multiProcessorCount;
+    std::string name = std::string(prop.gcnArchName) + ":" + prop.name;
+    std::replace(name.begin(), name.end(), ' ', '_');
+    set_device_name(name);
+    g_dev_ready = true;
+    return WPK_OK;
+}
+
+// Tap table of a problem: for reduction row kk = (c*R + r)*S + s the element offset of the tap
+// inside one image, c*H*W + r*dil_h*W + s*dil_w, and the tap number r*S+s; padding rows get 63.
+static std::vector<int32_t> build_tap_table(const Problem &pr)
+{
+    const wpk_conv_desc &d = pr.d;
+    std::vector<int32_t> t((size_t)pr.CRSpad * 2);
+    for (int kk = 0; kk < pr.CRSpad; ++kk) {
+        if (kk < pr.CRS) {
+            int s = kk % d.s, r = (kk / d.s) % d.r, c = kk / (d.s * d.r);
+            t[2 * kk] = c * d.h * d.w + r * d.dil_h * d.w + s * d.dil_w;
+            t[2 * kk + 1] = r * d.s + s;
+        } else {
+            t[2 * kk] = 0;
+            t[2 * kk + 1] = kMaxTaps;
+        }
+    }
+    return t;
+}
+
+static int upload_tap_table(const Problem &pr, int32_t **out)
+{
+    std::vector<int32_t> t = build_tap_table(pr);
+    int32_t *dptr = nullptr;
+    WPK_HIP(hipMalloc((void **)&dptr, t.size() * sizeof(int32_t)));
+    hipError_t e = hipMemcpy(dptr, t.data(), t.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(dptr);
+        set_last_hip_error((int)e);
+        return WPK_E_HIP;
+    }
+    *out = dptr;
+    return WPK_OK;
+}
+
+static int pack_weights(const Problem &pr, const float *w, float *wp, hipStream_t st)
+{
+    dim3 grid(pr.CRSpad / 32, pr.Kpad / 32);
+    hipLaunchKernelGGL(pack_weights_kernel, grid, dim3(256), 0, st, w, wp, pr.d.k, pr.CRS, pr.Kpad);
+    WPK_HIP(hipGetLastError());
+    return WPK_OK;
+}
+
+static int zero_fill(float *p, int64_t n, hipStream_t st)
+{
+    // y comes from the caller with 4-byte alignment only: peel to a 16-byte boundary
+    uintptr_t addr = (uintptr_t)p;
+    int head = (int)(((16 - (addr & 15)) & 15) / 4);
+    if (head > n) head = (int)n;
+    int64_t n4 = (n - head) / 4;
+    int tail = (int)(n - head - n4 * 4);
+    if (head) {
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(64), 0, st, (float4 *)nullptr, p, 0LL, head);
+        WPK_HIP(hipGetLastError());
+    }
+    int blocks = (int)std::min<int64_t>(2048, std::max<int64_t>(1, (n4 + 255) / 256));
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, (float4 *)(p + head),
+                       p + head + n4 * 4, (long long)n4, tail);
+    WPK_HIP(hipGetLastError());
+    return WPK_OK;
+}
+
+static int run_ref(const Problem &pr, const float *x, const float *w, float *y, float *dnorm,
+                   hipStream_t st)
+{
+    int blocks = (int)std::min<int64_t>(1 << 20, (pr.y_elems + 255) / 256);
+    hipLaunchKernelGGL(direct_conv_kernel, dim3(blocks), dim3(256), 0, st, x, w, y, dnorm, pr.d, pr.P,
+                       pr.Q, (long long)pr.y_elems);
+    WPK_HIP(hipGetLastError());
+    return WPK_OK;
+}
+
+// Launch one member of the tiled family.  cfg must be legal for pr (checked by the callers).
+static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32_t *ktab,
+                      const float *x, const float *wp, float *y, hipStream_t st)
+{
+    int vi = find_variant(cfg.bm, cfg.bn, cfg.bk, cfg.wm, cfg.wn);
+    if (vi < 0) return WPK_E_NO_CONFIG;
+    const wpk_conv_desc &d = pr.d;
+    IgemmArgs a;
+    a.x = x; a.wp = wp; a.y = y; a.ktab = ktab;
+    a.N = d.n; a.C = d.c; a.H = d.h; a.W = d.w; a.K = d.k; a.P = pr.P; a.Q = pr.Q; a.R = d.r; a.S = d.s;
+    a.stride_h = d.stride_h; a.stride_w = d.stride_w; a.pad_h = d.pad_h; a.pad_w = d.pad_w;
+    a.dil_h = d.dil_h; a.dil_w = d.dil_w;
+    a.M = (int32_t)pr.M; a.PQ = pr.P * pr.Q; a.HW = d.h * d.w; a.CRS = pr.CRS; a.Kpad = pr.Kpad;
+    a.nsteps = (pr.CRS + cfg.bk - 1) / cfg.bk;
+    a.split_k = cfg.split_k;
+    a.steps_per_split = (a.nsteps + cfg.split_k - 1) / cfg.split_k;
+    a.tiles_m = (int32_t)((pr.M + cfg.bm - 1) / cfg.bm);
+    a.tiles_n = (d.k + cfg.bn - 1) / cfg.bn;
+    a.remap = cfg.xcd_remap;
+    a.x_bytes = (uint32_t)(pr.x_elems * 4);
+    if (cfg.split_k > 1) {
+        int rc = zero_fill(y, pr.y_elems, st);
+        if (rc != WPK_OK) return rc;
+    }
+    WPK_HIP(kLaunch[vi](a, st));
+    return WPK_OK;
+}
+
+// ---- per-descriptor state of the one-shot entry points -------------------------------------------
+struct Prepared {
+    Problem pr;
+    int32_t *ktab;
+};
+static std::map<std::string, Prepared> g_prepared;
+static float *g_wscratch = nullptr;
+static size_t g_wscratch_elems = 0;
+
+static int get_prepared(const Problem &pr, Prepared **out)
+{
+    std::string key = desc_key(&pr.d);
+    auto it = g_prepared.find(key);
+    if (it == g_prepared.end()) {
+        Prepared p{pr, nullptr};
+        int rc = upload_tap_table(pr, &p.ktab);
+        if (rc != WPK_OK) return rc;
+        it = g_prepared.emplace(key, p).first;
+    }
+    *out = &it->second;
+    return WPK_OK;
+}
+
+static int get_wscratch(size_t elems, float **out)
+{
+    if (elems > g_wscratch_elems) {
+        if (g_wscratch) WPK_HIP(hipFree(g_wscratch));  // synchronises: earlier users are done
+        g_wscratch = nullptr;
+        g_wscratch_elems = 0;
+        WPK_HIP(hipMalloc((void **)&g_wscratch, elems * sizeof(float)));
+        g_wscratch_elems = elems;
+    }
+    *out = g_wscratch;
+    return WPK_OK;
+}
+
+static int check_io(const wpk_conv_desc *d, const void *x, const void *w, const void *y, Problem *pr)
+{
+    if (!d) return WPK_E_NULL_PTR;
+    int rc = make_problem(d, pr);
+    if (rc != WPK_OK) return rc;
+    if (!x || !w || !y) return WPK_E_NULL_PTR;
+    return WPK_OK;
+}
+
+static int fwd_with(const Problem &pr, const wpk_conv_config &cfg, const float *x, const float *w,
+                    float *y, hipStream_t st)
+{
+    std::lock_guard<std::mutex> g(g_mu);
+    Prepared *prep;
+    int rc = get_prepared(pr, &prep);
+    if (rc != WPK_OK) return rc;
+    float *wp;
+    rc = get_wscratch((size_t)pr.CRSpad * pr.Kpad, &wp);
+    if (rc != WPK_OK) return rc;
+    rc = pack_weights(pr, w, wp, st);
+    if (rc != WPK_OK) return rc;
+    return run_config(pr, cfg, prep->ktab, x, wp, y, st);
+}
+
+// ---- timing protocol of the tuner ------------------------------------------------------------------
+struct TuneCtx {
+    Problem pr;
+    wpk_tune_options opt;
+    hipStream_t st;
+    hipEvent_t e0, e1;
+    float *x, *w, *wp, *y, *yref, *dref;
+    unsigned *err_bits;
+    int32_t *ktab;
+    int rejected;
+    int hip_failed;
+    std::map<int, double> times_us;  // config id -> median microseconds
+};
+
+static int measure_us(TuneCtx &t, const wpk_conv_config &cfg, double *us_out, double *err_out)
+{
+    // one verification launch, compared on the device with the direct kernel's output
+    WPK_HIP(hipMemsetAsync(t.err_bits, 0, sizeof(unsigned), t.st));
+    int rc = run_config(t.pr, cfg, t.ktab, t.x, t.wp, t.y, t.st);
+    if (rc != WPK_OK) return rc;
+    hipLaunchKernelGGL(compare_kernel, dim3(512), dim3(256), 0, t.st, t.y, t.yref, t.dref,
+                       (long long)t.pr.y_elems, t.err_bits);
+    WPK_HIP(hipGetLastError());
+    unsigned bits = 0;
+    WPK_HIP(hipMemcpyAsync(&bits, t.err_bits, sizeof(unsigned), hipMemcpyDeviceToHost, t.st));
+    WPK_HIP(hipStreamSynchronize(t.st));
+    float err;
+    memcpy(&err, &bits, sizeof err);
+    *err_out = err;
+    if (!(err <= 1e-4f)) {
+        *us_out = 0.0;
+        return WPK_OK;
+    }
+    // estimate, then timed groups sized to last at least min_group_us
+    auto timed = [&](int launches, double *ms) -> int {
+        WPK_HIP(hipEventRecord(t.e0, t.st));
+        for (int i = 0; i < launches; ++i) {
+            int r = run_config(t.pr, cfg, t.ktab, t.x, t.wp, t.y, t.st);
+            if (r != WPK_OK) return r;
+        }
+        WPK_HIP(hipEventRecord(t.e1, t.st));
+        WPK_HIP(hipEventSynchronize(t.e1));
+        float f = 0;
+        WPK_HIP(hipEventElapsedTime(&f, t.e0, t.e1));
+        *ms = f;
+        return WPK_OK;
+    };
+    double ms = 0;
+    rc = timed(2, &ms);
+    if (rc != WPK_OK) return rc;
+    double est_us = std::max(ms * 1000.0 / 2, 0.5);
+    int group = (int)std::min(1000.0, std::max(1.0, ceil(t.opt.min_group_us / est_us)));
+    std::vector<double> samples;
+    for (int r = 0; r < std::max(1, t.opt.reps); ++r) {
+        rc = timed(group, &ms);
+        if (rc != WPK_OK) return rc;
+        samples.push_back(ms * 1000.0 / group);
+    }
+    std::sort(samples.begin(), samples.end());
+    *us_out = samples[samples.size() / 2];
+    return WPK_OK;
+}
+
+static int tune_constraint(const int32_t *genes, int32_t n, void *user)
+{
+    TuneCtx *t = (TuneCtx *)user;
+    wpk_conv_config cfg;
+    if (n != WPK_N_GENES || wpk_config_from_genes(genes, &cfg) != WPK_OK) return 0;
+    return legal_for(t->pr, cfg) ? 1 : 0;
+}
+
+// Step2: fitness = 1 / measured runtime; a candidate that fails verification gets 0.
+static double tune_fitness(const int32_t *genes, int32_t n, void *user)
+{
+    TuneCtx *t = (TuneCtx *)user;
+    wpk_conv_config cfg;
+    if (n != WPK_N_GENES || wpk_config_from_genes(genes, &cfg) != WPK_OK) return 0.0;
+    double us = 0, err = 0;
+    int rc = measure_us(*t, cfg, &us, &err);
+    if (rc != WPK_OK) {
+        t->hip_failed = rc;
+        return 0.0;
+    }
+    if (us <= 0.0) {
+        t->rejected++;
+        if (t->opt.verbose)
+            fprintf(stderr, "[wpk tune] rejected %s split %d: normalised error %.3g\n",
+                    wpk_config_kernel_name(&cfg), cfg.split_k, err);
+        return 0.0;
+    }
+    t->times_us[wpk_config_id(&cfg)] = us;
+    return 1.0 / us;
+}
+
+static void tune_free(TuneCtx &t)
+{
+    if (t.x) (void)hipFree(t.x);
+    if (t.w) (void)hipFree(t.w);
+    if (t.wp) (void)hipFree(t.wp);
+    if (t.y) (void)hipFree(t.y);
+    if (t.yref) (void)hipFree(t.yref);
+    if (t.dref) (void)hipFree(t.dref);
+    if (t.err_bits) (void)hipFree(t.err_bits);
+    if (t.ktab) (void)hipFree(t.ktab);
+    if (t.e0) (void)hipEventDestroy(t.e0);
+    if (t.e1) (void)hipEventDestroy(t.e1);
+    if (t.st) (void)hipStreamDestroy(t.st);
+}
+
+static int tune_setup(TuneCtx &t)
+{
+    const Problem &pr = t.pr;
+    WPK_HIP(hipStreamCreate(&t.st));
+    WPK_HIP(hipEventCreate(&t.e0));
+    WPK_HIP(hipEventCreate(&t.e1));
+    WPK_HIP(hipMalloc((void **)&t.x, pr.x_elems * 4));
+    WPK_HIP(hipMalloc((void **)&t.w, pr.w_elems * 4));
+    WPK_HIP(hipMalloc((void **)&t.wp, (size_t)pr.CRSpad * pr.Kpad * 4));
+    WPK_HIP(hipMalloc((void **)&t.y, pr.y_elems * 4));
+    WPK_HIP(hipMalloc((void **)&t.yref, pr.y_elems * 4));
+    WPK_HIP(hipMalloc((void **)&t.dref, pr.y_elems * 4));
+    WPK_HIP(hipMalloc((void **)&t.err_bits, sizeof(unsigned)));
+    int rc = upload_tap_table(pr, &t.ktab);
+    if (rc != WPK_OK) return rc;
+    float wscale = sqrtf(6.0f / (float)pr.CRS);  // uniform with the variance of Kaiming-normal
+    hipLaunchKernelGGL(fill_hash_kernel, dim3(1024), dim3(256), 0, t.st, t.x, (long long)pr.x_elems,
+                       0x1234u, 0.0f, 1.0f);
+    hipLaunchKernelGGL(fill_hash_kernel, dim3(1024), dim3(256), 0, t.st, t.w, (long long)pr.w_elems,
+                       0x9876u, -wscale, wscale);
+    WPK_HIP(hipGetLastError());
+    rc = pack_weights(pr, t.w, t.wp, t.st);
+    if (rc != WPK_OK) return rc;
+    rc = run_ref(pr, t.x, t.w, t.yref, t.dref, t.st);
+    if (rc != WPK_OK) return rc;
+    WPK_HIP(hipStreamSynchronize(t.st));
+    return WPK_OK;
+}
+
+}  // namespace wpk
+
+using namespace wpk;
+
+// ---- plans ------------------------------------------------------------------------------------------
+struct wpk_plan {
+    struct Layer {
+        Problem pr;
+        wpk_conv_config cfg;
+        int unique;
+        float *wp;
+        bool has_w;
+    };
+    std::vector<Layer> layers;
+    std::vector<int32_t *> ktabs;  // one per distinct descriptor
+};
+
+extern "C" {
+
+int wpk_device_info(char *name, int32_t cap, int32_t *cus)
+{
+    std::lock_guard<std::mutex> g(g_mu);
+    int rc = ensure_device();
+    if (rc != WPK_OK) return rc;
+    if (name && cap > 0) {
+        strncpy(name, device_name().c_str(), cap - 1);
+        name[cap - 1] = 0;
+    }
+    if (cus) *cus = g_cus;
+    return WPK_OK;
+}
+
+int wpk_config_default(const wpk_conv_desc *d, wpk_conv_config *out)
+{
+    if (!out) return WPK_E_NULL_PTR;
+    Problem pr;
+    int rc = make_problem(d, &pr);
+    if (rc != WPK_OK) return rc;
+    if (!pr.tiled_ok) return WPK_E_UNSUPPORTED;
+    default_config(pr, g_cus, out);
+    return WPK_OK;
+}
+
+int wpk_conv2d_ref(const wpk_conv_desc *d, const float *x, const float *w, float *y, void *stream)
+{
+    Problem pr;
+    int rc = check_io(d, x, w, y, &pr);
+    if (rc != WPK_OK) return rc;
+    return run_ref(pr, x, w, y, nullptr, (hipStream_t)stream);
+}
+
+int wpk_conv2d_fwd_config(const wpk_conv_desc *d, const wpk_conv_config *cfg, const float *x,
+                          const float *w, float *y, void *stream)
+{
+    Problem pr;
+    int rc = check_io(d, x, w, y, &pr);
+    if (rc != WPK_OK) return rc;
+    if (!cfg) return WPK_E_NULL_PTR;
+    if (!legal_for(pr, *cfg)) return WPK_E_NO_CONFIG;
+    return fwd_with(pr, *cfg, x, w, y, (hipStream_t)stream);
+}
+
+int wpk_conv2d_fwd(const wpk_conv_desc *d, const float *x, const float *w, float *y, void *stream)
+{
+    Problem pr;
+    int rc = check_io(d, x, w, y, &pr);
+    if (rc != WPK_OK) return rc;
+    if (!pr.tiled_ok) return run_ref(pr, x, w, y, nullptr, (hipStream_t)stream);
+    {
+        std::lock_guard<std::mutex> g(g_mu);
+        rc = ensure_device();
+        if (rc != WPK_OK) return rc;
+    }
+    wpk_conv_config cfg;
+    if (wpk_cache_lookup(d, &cfg) != 1 || !legal_for(pr, cfg)) default_config(pr, g_cus, &cfg);
+    return fwd_with(pr, cfg, x, w, y, (hipStream_t)stream);
+}
+
+int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int force,
+                     wpk_tune_report *report)
+{
+    Problem pr;
+    int rc = make_problem(d, &pr);
+    if (rc != WPK_OK) return rc;
+    if (!pr.tiled_ok) return WPK_E_UNSUPPORTED;
+    {
+        std::lock_guard<std::mutex> g(g_mu);
+        rc = ensure_device();
+        if (rc != WPK_OK) return rc;
+    }
+    wpk_conv_config cached;
+    if (!force && wpk_cache_lookup(d, &cached) == 1 && legal_for(pr, cached)) {
+        if (report) {
+            memset(report, 0, sizeof *report);
+            report->best = cached;
+        }
+        return wpk_config_id(&cached);
+    }
+    auto t_start = std::chrono::steady_clock::now();
+    TuneCtx t;
+    t.pr = pr;
+    if (opt_in) t.opt = *opt_in; else wpk_tune_default_options(&t.opt);
+    t.st = nullptr; t.e0 = t.e1 = nullptr;
+    t.x = t.w = t.wp = t.y = t.yref = t.dref = nullptr;
+    t.err_bits = nullptr; t.ktab = nullptr;
+    t.rejected = 0; t.hip_failed = 0;
+    rc = tune_setup(t);
+    if (rc != WPK_OK) {
+        tune_free(t);
+        return rc;
+    }
+    wpk_conv_config defcfg;
+    default_config(pr, g_cus, &defcfg);
+    double def_us = 0, def_err = 0;
+    rc = measure_us(t, defcfg, &def_us, &def_err);
+    if (rc != WPK_OK) {
+        tune_free(t);
+        return rc;
+    }
+    int32_t lo[WPK_N_GENES], hi[WPK_N_GENES], best_genes[WPK_N_GENES];
+    wpk_config_gene_ranges(lo, hi);
+    double best_f = 0;
+    int32_t evals = 0;
+    int gens = 0;
+    if (t.opt.mode == 2) {  // exhaustive: every legal chromosome once
+        int32_t g[WPK_N_GENES] = {0};
+        for (;;) {
+            if (tune_constraint(g, WPK_N_GENES, &t)) {
+                double f = tune_fitness(g, WPK_N_GENES, &t);
+                ++evals;
+                if (f > best_f) {
+                    best_f = f;
+                    memcpy(best_genes, g, sizeof g);
+                }
+            }
+            int i = 0;
+            while (i < WPK_N_GENES && ++g[i] > hi[i]) g[i++] = 0;
+            if (i == WPK_N_GENES) break;
+        }
+        gens = 1;
+    } else {
+        gens = wpk_ga_search(WPK_N_GENES, lo, hi, tune_constraint, tune_fitness, &t, &t.opt,
+                             best_genes, &best_f, &evals, nullptr, nullptr, nullptr, 0);
+    }
+    int result;
+    if (t.hip_failed) {
+        result = t.hip_failed;
+    } else if (gens < 0) {
+        result = gens;
+    } else if (!(best_f > 0.0)) {
+        result = WPK_E_VERIFY;
+    } else {
+        wpk_conv_config best;
+        wpk_config_from_genes(best_genes, &best);
+        double best_us = 1.0 / best_f;
+        if (def_us > 0.0 && def_us < best_us) {  // never hand back something slower than the default
+            best = defcfg;
+            best_us = def_us;
+        }
+        wpk_cache_store(d, &best, best_us);
+        if (report) {
+            report->best = best;
+            report->best_us = best_us;
+            report->default_us = def_us;
+            report->evaluations = evals;
+            report->generations = gens;
+            report->rejected = t.rejected;
+            report->seconds =
+                std::chrono::duration<double>(std::chrono::steady_clock::now() - t_start).count();
+        }
+        result = wpk_config_id(&best);
+    }
+    tune_free(t);
+    return result;
+}
+
+int wpk_conv_tune(const wpk_conv_desc *d) { return wpk_conv_tune_ex(d, nullptr, 0, nullptr); }
+
+int wpk_conv_plan(const wpk_conv_desc *layers, int32_t n_layers, int32_t tune, wpk_plan **out)
+{
+    if (!layers || !out) return WPK_E_NULL_PTR;
+    if (n_layers <= 0) return WPK_E_BAD_ARG;
+    {
+        std::lock_guard<std::mutex> g(g_mu);
+        int rc = ensure_device();
+        if (rc != WPK_OK) return rc;
+    }
+    wpk_plan *plan = new wpk_plan();
+    std::map<std::string, int> seen;  // identical descriptors share one search and one tap table
+    int rc = WPK_OK;
+    for (int i = 0; i < n_layers && rc == WPK_OK; ++i) {
+        wpk_plan::Layer L;
+        rc = make_problem(&layers[i], &L.pr);
+        if (rc != WPK_OK) break;
+        if (!L.pr.tiled_ok) { rc = WPK_E_UNSUPPORTED; break; }
+        L.wp = nullptr;
+        L.has_w = false;
+        std::string key = desc_key(&layers[i]);
+        auto it = seen.find(key);
+        if (it == seen.end()) {
+            int32_t *ktab = nullptr;
+            rc = upload_tap_table(L.pr, &ktab);
+            if (rc != WPK_OK) break;
+            plan->ktabs.push_back(ktab);
+            it = seen.emplace(key, (int)plan->ktabs.size() - 1).first;
+            if (tune) {
+                int id = wpk_conv_tune(&layers[i]);
+                if (id < 0) { rc = id; break; }
+            }
+        }
+        L.unique = it->second;
+        if (wpk_cache_lookup(&layers[i], &L.cfg) != 1 || !legal_for(L.pr, L.cfg))
+            default_config(L.pr, g_cus, &L.cfg);
+        hipError_t e = hipMalloc((void **)&L.wp, (size_t)L.pr.CRSpad * L.pr.Kpad * sizeof(float));
+        if (e != hipSuccess) { set_last_hip_error((int)e); rc = WPK_E_HIP; break; }
+        plan->layers.push_back(L);
+    }
+    if (rc != WPK_OK) {
+        wpk_plan_destroy(plan);
+        return rc;
+    }
+    *out = plan;
+    return WPK_OK;
+}
+
+int wpk_plan_set_weights(wpk_plan *plan, int32_t layer, const float *w, void *stream)
+{
+    if (!plan || !w) return WPK_E_NULL_PTR;
+    if (layer < 0 || layer >= (int)plan->layers.size()) return WPK_E_BAD_ARG;
+    wpk_plan::Layer &L = plan->layers[layer];
+    int rc = pack_weights(L.pr, w, L.wp, (hipStream_t)stream);
+    if (rc == WPK_OK) L.has_w = true;
+    return rc;
+}
+
+int wpk_plan_run_layer(wpk_plan *plan, int32_t layer, const float *x, float *y, void *stream)
+{
+    if (!plan || !x || !y) return WPK_E_NULL_PTR;
+    if (layer < 0 || layer >= (int)plan->layers.size()) return WPK_E_BAD_ARG;
+    wpk_plan::Layer &L = plan->layers[layer];
+    if (!L.has_w) return WPK_E_BAD_ARG;
+    return run_config(L.pr, L.cfg, plan->ktabs[L.unique], x, L.wp, y, (hipStream_t)stream);
+}
+
+int wpk_plan_run(wpk_plan *plan, const float *const *x, float *const *y, void *stream)
+{
+    if (!plan || !x || !y) return WPK_E_NULL_PTR;
+    for (size_t i = 0; i < plan->layers.size(); ++i) {
+        int rc = wpk_plan_run_layer(plan, (int32_t)i, x[i], y[i], stream);
+        if (rc != WPK_OK) return rc;
+    }
+    return WPK_OK;
+}
+
+int wpk_plan_num_layers(const wpk_plan *plan) { return plan ? (int)plan->layers.size() : WPK_E_NULL_PTR; }
+int wpk_plan_num_unique(const wpk_plan *plan) { return plan ? (int)plan->ktabs.size() : WPK_E_NULL_PTR; }
+
+int wpk_plan_layer_config(const wpk_plan *plan, int32_t layer, wpk_conv_config *out)
+{
+    if (!plan || !out) return WPK_E_NULL_PTR;
+    if (layer < 0 || layer >= (int)plan->layers.size()) return WPK_E_BAD_ARG;
+    *out = plan->layers[layer].cfg;
+    return WPK_OK;
+}
+
+int wpk_plan_set_layer_config(wpk_plan *plan, int32_t layer, const wpk_conv_config *cfg)
+{
+    if (!plan || !cfg) return WPK_E_NULL_PTR;
+    if (layer < 0 || layer >= (int)plan->layers.size()) return WPK_E_BAD_ARG;
+    if (!legal_for(plan->layers[layer].pr, *cfg)) return WPK_E_NO_CONFIG;
+    plan->layers[layer].cfg = *cfg;
+    return WPK_OK;
+}
+
+void wpk_plan_destroy(wpk_plan *plan)
+{
+    if (!plan) return;
+    for (auto &L : plan->layers)
+        if (L.wp) (void)hipFree(L.wp);
+    for (int32_t *t : plan->ktabs)
+        if (t) (void)hipFree(t);
+    delete plan;
+}
+
+}  // extern "C"

@@ -1,0 +1,83 @@
+// Internal declarations shared by the translation units of libwpk.  Not part of the ABI.
+#ifndef WPK_INTERNAL_H
+#define WPK_INTERNAL_H
+
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "wpk.h"
+
+namespace wpk {
+
+// ---- gene value lists (the search sees index ranges into them) -------------------------------
+extern const int32_t kBmVals[3];     // 64, 128, 256
+extern const int32_t kBnVals[3];     // 32, 64, 128
+extern const int32_t kBkVals[3];     // 8, 16, 32
+extern const int32_t kWmVals[3];     // 1, 2, 4
+extern const int32_t kWnVals[3];     // 1, 2, 4
+extern const int32_t kSplitVals[9];  // 1, 2, 3, 4, 6, 8, 9, 12, 16
+extern const int32_t kRemapVals[2];  // 0, 1
+extern const int kGeneCounts[WPK_N_GENES];
+const int32_t *gene_values(int g);
+
+// Reduction entries are padded up to a multiple of kRedAlign rows (the largest K-step) and
+// packed output channels to a multiple of kKoutAlign (the largest channel tile), so tile loads
+// of packed weights and of the tap table never need a bounds check.
+static const int kRedAlign = 32;
+static const int kKoutAlign = 128;
+// Filter taps are tracked in a 64-bit in-bounds mask per pixel; bit 63 is the "never valid"
+// sentinel used by padded reduction rows, so a filter may have at most 63 taps.
+static const int kMaxTaps = 63;
+static const int kNumXcd = 8;
+static const int kMaxLdsBytes = 64 * 1024;
+// Activation offsets are 32-bit byte offsets with 0x80000000 as the out-of-range marker.
+static const int64_t kMaxTiledBytes = 0x7fffffff;
+
+// ---- one compiled tile combination -------------------------------------------------------------
+struct Variant {
+    int32_t bm, bn, bk, wm, wn;
+    const char *name;
+};
+extern const Variant kVariants[];
+extern const int kNumVariants;
+int find_variant(int bm, int bn, int bk, int wm, int wn);  // index or -1
+
+// ---- everything derived from one descriptor ------------------------------------------------------
+struct Problem {
+    wpk_conv_desc d;
+    int32_t P, Q;
+    int64_t M;       // N*P*Q output pixels (GEMM columns)
+    int32_t CRS;     // reduction length
+    int32_t CRSpad;  // rounded up to kRedAlign
+    int32_t Kpad;    // K rounded up to kKoutAlign
+    int64_t x_elems, w_elems, y_elems;
+    bool tiled_ok;   // the tiled family can run it (else only the direct kernel)
+};
+int make_problem(const wpk_conv_desc *d, Problem *out);  // WPK_OK or a WPK_E_* code
+std::string desc_key(const wpk_conv_desc *d);
+
+// Kernel argument block of the tiled implicit-GEMM family (passed by value).
+struct IgemmArgs {
+    const float *x;
+    const float *wp;      // packed weights [CRSpad][Kpad], reduction-major
+    float *y;
+    const int32_t *ktab;  // [CRSpad][2]: element offset of the tap in x, tap index r*S+s (63 = pad)
+    int32_t N, C, H, W, K, P, Q, R, S;
+    int32_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+    int32_t M, PQ, HW, CRS, Kpad;
+    int32_t nsteps, steps_per_split, split_k;
+    int32_t tiles_m, tiles_n, remap;
+    uint32_t x_bytes;
+};
+
+// host-side state shared between wpk_host.cpp and wpk_api.hip
+void set_last_hip_error(int e);
+void set_device_name(const std::string &name);
+const std::string &device_name();
+bool legal_for(const Problem &pr, const wpk_conv_config &cfg);
+void default_config(const Problem &pr, int compute_units, wpk_conv_config *out);
+
+}  // namespace wpk
+#endif

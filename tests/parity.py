@@ -1,0 +1,71 @@
+"""Helpers shared by the GPU parity tests: run the HIP path through the C ABI on seeded
+inputs and compare with the CPU oracle element by element.
+
+Tolerance (fp32 arithmetic): |y_gpu - y_oracle| <= 1e-4 * D per output, D = sum |x*w| over the
+output's taps (fp64, from the oracle); where D == 0 the GPU value must be exactly 0."""
+import numpy as np
+
+from oracle import conv as oc
+from paper_2008_04567_amd import binding as B
+from paper_2008_04567_amd import workloads as W
+
+TOL = 1e-4
+
+
+def torch_dev():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return torch, torch.device("cuda:0")
+
+
+def to_dev(a):
+    torch, dev = torch_dev()
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
+def oracle_full(layer, x, w):
+    sh = oc.shape_from_layer(layer)
+    y, d, _ = oc.conv2d(sh, x, w)
+    return y, d
+
+
+def assert_close(y_gpu, y_ref, d_ref, what=""):
+    y_gpu = np.asarray(y_gpu, dtype=np.float64).reshape(y_ref.shape)
+    assert np.all(np.isfinite(y_gpu)), what + ": non-finite output"
+    zero = d_ref == 0
+    assert np.all(y_gpu[zero] == 0.0), what + ": nonzero output where no tap contributes"
+    err = np.abs(y_gpu - y_ref) / np.where(zero, 1.0, d_ref)
+    worst = float(err.max()) if err.size else 0.0
+    assert worst <= TOL, "%s: max normalised error %.3g > %g" % (what, worst, TOL)
+    return worst
+
+
+def run_gpu(layer, x, w, cfg=None, mode="fwd"):
+    """One convolution through the C ABI; returns the output as a NumPy array."""
+    torch, dev = torch_dev()
+    desc = B.make_desc(layer)
+    P, Q = B.conv_out_shape(desc)
+    xd, wd = to_dev(x), to_dev(w)
+    # canary-filled output with guard bands to catch stray writes
+    n_out = layer["n"] * layer["k"] * P * Q
+    guard = 256
+    buf = torch.full((n_out + 2 * guard,), 12345.0, device=dev, dtype=torch.float32)
+    yd = buf[guard:guard + n_out]
+    if mode == "ref":
+        B.conv2d_ref(desc, xd, wd, yd)
+    elif cfg is not None:
+        B.conv2d_fwd_config(desc, cfg, xd, wd, yd)
+    else:
+        B.conv2d_fwd(desc, xd, wd, yd)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    assert np.all(host[:guard] == 12345.0) and np.all(host[guard + n_out:] == 12345.0), \
+        "write outside the output tensor"
+    return host[guard:guard + n_out].reshape(layer["n"], layer["k"], P, Q)
+
+
+def check_layer(layer, cfg=None, mode="fwd", what=None):
+    x, w = W.make_inputs(layer)
+    y_ref, d_ref = oracle_full(layer, x, w)
+    y = run_gpu(layer, x, w, cfg=cfg, mode=mode)
+    return assert_close(y, y_ref, d_ref, what or layer["name"])

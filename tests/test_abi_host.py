@@ -1,0 +1,234 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+and its host logic (descriptor validation, output-size rule, configuration encoding and
+constraint check, cache, search engine) behaves as the header says.  No compute call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import conv as oc
+from oracle import ga as oga
+from paper_2008_04567_amd import binding as B
+from paper_2008_04567_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "wpk.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(wpk_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(n for n in names if not n.endswith("_fn")))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = B.lib()
+    names = header_functions()
+    assert len(names) >= 35
+    for n in names:
+        assert hasattr(L, n), "missing export " + n
+    assert set(L._signatures) == set(names), "binding and header disagree"
+    assert "gfx950" in B.version()
+
+
+def test_struct_layouts_match_the_header(tmp_path):
+    """Sizes and field offsets as a C compiler sees the header, against the ctypes mirrors."""
+    import subprocess
+    src = tmp_path / "sizes.c"
+    src.write_text("""#include <stdio.h>
+#include <stddef.h>
+#include "wpk.h"
+int main(void) {
+  printf("%zu %zu %zu %zu %zu %zu %zu %zu\\n", sizeof(wpk_conv_desc), sizeof(wpk_conv_config),
+         sizeof(wpk_tune_options), sizeof(wpk_tune_report), offsetof(wpk_tune_options, seed),
+         offsetof(wpk_tune_options, min_group_us), offsetof(wpk_tune_report, best_us),
+         offsetof(wpk_tune_report, seconds));
+  return 0; }
+""")
+    exe = tmp_path / "sizes"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    got = [int(v) for v in subprocess.run([str(exe)], check=True, capture_output=True,
+                                          text=True).stdout.split()]
+    assert got == [ctypes.sizeof(B.ConvDesc), ctypes.sizeof(B.ConvConfig),
+                   ctypes.sizeof(B.TuneOptions), ctypes.sizeof(B.TuneReport),
+                   B.TuneOptions.seed.offset, B.TuneOptions.min_group_us.offset,
+                   B.TuneReport.best_us.offset, B.TuneReport.seconds.offset]
+    assert got[0] == 60 and got[1] == 28
+
+
+def d13(n, c, h, w, k, r, s, st=(1, 1), pd=(0, 0), dl=(1, 1)):
+    return B.make_desc(dict(n=n, c=c, h=h, w=w, k=k, r=r, s=s, stride_h=st[0], stride_w=st[1],
+                            pad_h=pd[0], pad_w=pd[1], dil_h=dl[0], dil_w=dl[1]))
+
+
+def test_out_shape_agrees_with_the_oracle_rule_over_a_sweep():
+    import itertools
+    for h, w, r, s, sh, sw, ph, pw, dh, dw in itertools.product(
+            [1, 5, 8, 13], [3, 9], [1, 3, 4], [1, 2, 5], [1, 2, 3], [1, 2], [0, 1, 3], [0, 2],
+            [1, 2], [1, 3]):
+        ref = oc.out_shape(oc.make_shape(1, 1, h, w, 1, r, s, (sh, sw), (ph, pw), (dh, dw)))
+        d = d13(1, 1, h, w, 1, r, s, (sh, sw), (ph, pw), (dh, dw))
+        if ref is None:
+            assert B.lib().wpk_conv_out_shape(ctypes.byref(d), None, None) == B.E_BAD_DESC
+        else:
+            assert B.conv_out_shape(d) == ref
+
+
+def test_workload_shapes_and_flops():
+    want = {"stem": 112, "s1b0.c2": 56, "s2b0.c2": 28, "s3b0.c2": 14, "s4b0.c2": 7,
+            "s2b0.proj": 28, "s4b2.c3": 7}
+    total = 0.0
+    for l in W.resnet50_stack(1):
+        d = B.make_desc(l)
+        p, q = B.conv_out_shape(d)
+        if l["name"] in want:
+            assert (p, q) == (want[l["name"]],) * 2
+        total += B.conv_flops(d)
+    assert abs(total / 1e9 - 8.174) < 0.01
+    for l in W.config3():
+        assert abs(B.conv_flops(B.make_desc(l)) / 1e9 - 3.699) < 0.001
+
+
+def test_error_codes():
+    L = B.lib()
+    good = d13(1, 4, 8, 8, 4, 3, 3, pd=(1, 1))
+    assert L.wpk_conv_out_shape(None, None, None) == B.E_NULL_PTR
+    for field, val in [("n", 0), ("c", -1), ("stride_h", 0), ("dil_w", 0), ("pad_h", -1), ("k", 0)]:
+        bad = d13(1, 4, 8, 8, 4, 3, 3, pd=(1, 1))
+        setattr(bad, field, val)
+        assert L.wpk_conv_out_shape(ctypes.byref(bad), None, None) == B.E_BAD_DESC
+    assert L.wpk_conv_out_shape(ctypes.byref(d13(1, 1, 2, 2, 1, 3, 3)), None, None) == B.E_BAD_DESC
+    bad = d13(1, 4, 8, 8, 4, 3, 3)
+    bad.dtype = 1
+    assert L.wpk_conv_out_shape(ctypes.byref(bad), None, None) == B.E_UNSUPPORTED
+    bad = d13(1, 4, 8, 8, 4, 3, 3)
+    bad.layout = 1
+    assert L.wpk_conv_out_shape(ctypes.byref(bad), None, None) == B.E_UNSUPPORTED
+    # null tensors are rejected before anything touches the GPU
+    assert L.wpk_conv2d_fwd(ctypes.byref(good), None, None, None, None) == B.E_NULL_PTR
+    assert L.wpk_conv2d_ref(ctypes.byref(good), None, None, None, None) == B.E_NULL_PTR
+    assert L.wpk_conv2d_fwd(None, None, None, None, None) == B.E_NULL_PTR
+    assert B.conv_flops(bad) == 0.0
+    for s in range(-8, 1):
+        assert B.status_string(s) and "unknown" not in B.status_string(s)
+    assert "unknown" in B.status_string(-99)
+
+
+def test_config_encoding_roundtrip_and_constraint_check():
+    lo, hi = B.config_gene_ranges()
+    assert lo == [0] * 7 and hi == [2, 2, 2, 2, 2, 8, 1]
+    d = B.make_desc(W.config3()[1])
+    legal = B.legal_configs(d)
+    assert 300 < len(legal) < 2000
+    ids = set()
+    for c in legal:
+        cid = B.config_id(c)
+        assert B.config_from_id(cid).astuple() == c.astuple()
+        assert B.config_from_genes(B.config_to_genes(c)).astuple() == c.astuple()
+        assert B.config_kernel_name(c).startswith("wpk_igemm_%dx%dx%d_" % (c.bm, c.bn, c.bk))
+        # the constraints the header states
+        assert 64 * c.wm * c.wn <= 1024
+        assert 2 * c.bk * (c.bm + c.bn) * 4 <= 64 * 1024
+        assert (c.bm // c.wm) % 32 == 0 and (c.bn // c.wn) % 32 == 0
+        ids.add(cid)
+    assert len(ids) == len(legal)
+    assert not B.config_legal(d, B.make_config(128, 64, 16, 1, 1))          # not built
+    assert not B.config_legal(d, B.make_config(100, 64, 16, 2, 2))          # not in the list
+    tiny = d13(1, 1, 4, 4, 8, 1, 1)                                            # 1 reduction step
+    assert not B.config_legal(tiny, B.make_config(128, 64, 16, 2, 2, split_k=2))
+    assert B.config_legal(tiny, B.make_config(128, 64, 16, 2, 2, split_k=1))
+    big_filter = d13(1, 1, 20, 20, 8, 8, 8)                                    # 64 taps > 63
+    assert B.legal_configs(big_filter) == []
+    with pytest.raises(B.WpkError):
+        B.config_from_id(10 ** 9)
+    with pytest.raises(B.WpkError):
+        B.config_id(B.make_config(100, 64, 16, 2, 2))
+
+
+def test_default_config_is_legal_for_every_workload_layer():
+    layers = (W.config1() + W.config2() + W.config3() + W.config4() + W.resnet50_stack(1)
+              + W.resnet50_stack(16) + W.table1_convs())
+    for l in layers:
+        d = B.make_desc(l)
+        assert B.config_legal(d, B.config_default(d)), l["name"]
+
+
+def test_cache_roundtrip_and_identity_criterion(tmp_path):
+    B.cache_clear()
+    a, b = W.config3()[0], W.config3()[1]
+    da, db = B.make_desc(a), B.make_desc(b)
+    assert B.cache_lookup(da) is None
+    ca = B.make_config(128, 64, 16, 2, 2, 1, 0)
+    B.cache_store(da, ca, 12.5)
+    assert B.cache_lookup(da).astuple() == ca.astuple()
+    assert B.cache_lookup(db) is None
+    # any differing field is a different operator
+    for f in ("n", "pad_h", "dil_w", "stride_w", "k"):
+        other = B.make_desc(a)
+        setattr(other, f, getattr(other, f) + 1)
+        if B.lib().wpk_conv_out_shape(ctypes.byref(other), None, None) == 0:
+            assert B.cache_lookup(other) is None
+    with pytest.raises(B.WpkError):
+        B.cache_store(da, B.make_config(128, 64, 16, 1, 1))
+    path = str(tmp_path / "cache.txt")
+    B.cache_save(path)
+    B.cache_clear()
+    assert B.cache_size() == 0
+    assert B.cache_load(path) == 1
+    assert B.cache_lookup(da).astuple() == ca.astuple()
+    with pytest.raises(B.WpkError):
+        B.cache_load(str(tmp_path / "missing.txt"))
+    B.cache_clear()
+
+
+# ---- the search engine against the step-by-step oracle ------------------------------------------
+LO, HI = [0, 0, 0, 0], [7, 5, 9, 3]
+
+
+def fit_sep(ch):
+    return 1.0 / (1.0 + sum((a - b) ** 2 for a, b in zip(ch, (5, 2, 7, 1))))
+
+
+def fit_rugged(ch):
+    a, b, c, d = ch
+    return 1.0 / (10.0 + abs(a * b - 12) + 0.5 * abs(c - 2 * d) + ((a + c) % 3) * 0.7)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 7, 2008])
+@pytest.mark.parametrize("fit,cons", [(fit_sep, None), (fit_rugged, lambda ch: sum(ch) % 2 == 0),
+                                      (fit_rugged, lambda ch: ch[0] != ch[1])])
+def test_engine_matches_oracle_generation_by_generation(seed, fit, cons):
+    kw = dict(pop=16, elites=3, next_pop=12, participants=10, pm=0.2, eps=0.01, patience=4,
+              max_gen=9)
+    ref = oga.genetic_search(LO, HI, cons or (lambda ch: True), fit, seed=seed, retries=8, **kw)
+    opt = B.tune_default_options(population=16, elites=3, next_population=12, participants=10,
+                                 mutation=0.2, eps=0.01, patience=4, max_generations=9, seed=seed)
+    got = B.ga_search(LO, HI, cons, fit, opt, history_capacity=9)
+    assert got["generations"] == len(ref["history"])
+    assert got["history"] == ref["history"]            # same chromosomes, same fitness, bit for bit
+    assert got["best"] == ref["best"]
+    assert got["best_fitness"] == ref["best_fitness"]
+    assert got["evaluations"] == ref["evaluations"]
+
+
+def test_engine_default_sizes_and_flat_fitness():
+    opt = B.tune_default_options(seed=3)
+    ref = oga.genetic_search(LO, HI, lambda ch: True, fit_sep, seed=3, pop=24, elites=4, pm=0.15,
+                             eps=0.03, patience=4, max_gen=12)
+    got = B.ga_search(LO, HI, None, fit_sep, opt, history_capacity=12)
+    assert got["history"] == ref["history"]
+    flat = B.ga_search(LO, HI, None, lambda ch: 2.0, opt, history_capacity=12)
+    assert flat["generations"] == 1
+
+
+def test_engine_random_mode_and_bad_arguments():
+    opt = B.tune_default_options(seed=5, mode=1, max_generations=5, patience=0, eps=0.0)
+    got = B.ga_search(LO, HI, None, fit_sep, opt, history_capacity=5)
+    assert got["generations"] == 5
+    assert all(len(p) == 24 for p, _ in got["history"])
+    with pytest.raises(B.WpkError):
+        B.ga_search([0, 3], [1, 2], None, fit_sep)       # empty gene range
+    with pytest.raises(B.WpkError):
+        B.ga_search([0], [3], lambda ch: False, lambda ch: 1.0)   # nothing is legal

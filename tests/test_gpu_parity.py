@@ -1,0 +1,137 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs, element by element.  Tolerance: 1e-4 * sum|x*w| per output (tests/parity.py)."""
+import ctypes
+
+import numpy as np
+import pytest
+
+from paper_2008_04567_amd import binding as B
+from paper_2008_04567_amd import workloads as W
+from tests import parity as PT
+
+pytestmark = pytest.mark.gpu
+
+# several tiles in both dimensions with ragged tails against every tile size:
+# M = 2*19*23 = 874 pixels, K = 72 channels, reduction 20*9 = 180
+RAGGED = W.layer("ragged", 2, 20, (19, 23), 72, 3, 1, 1, x_dist="u11", w_dist="u11", seed=77)
+
+
+def test_extension_is_loaded_and_sees_the_gpu():
+    name, cus = B.device_info()
+    print("device", name, cus, flush=True)
+    assert "gfx950" in name and cus >= 1
+
+
+def test_reference_kernel_configs_1_and_2():
+    for l in W.config1() + W.config2():
+        print(l["name"], flush=True)
+        PT.check_layer(l, mode="ref")
+
+
+def test_default_path_configs_1_and_2():
+    for l in W.config1() + W.config2():
+        print(l["name"], flush=True)
+        PT.check_layer(l)
+
+
+def test_every_tile_variant_on_a_ragged_shape():
+    desc = B.make_desc(RAGGED)
+    x, w = W.make_inputs(RAGGED)
+    y_ref, d_ref = PT.oracle_full(RAGGED, x, w)
+    cfgs = B.legal_configs(desc, split_k=[1], xcd_remap=1)
+    assert len(cfgs) >= 40
+    for c in cfgs:
+        print(c, flush=True)
+        y = PT.run_gpu(RAGGED, x, w, cfg=c)
+        PT.assert_close(y, y_ref, d_ref, repr(c))
+
+
+def test_split_k_and_remap_settings():
+    desc = B.make_desc(RAGGED)
+    x, w = W.make_inputs(RAGGED)
+    y_ref, d_ref = PT.oracle_full(RAGGED, x, w)
+    for (bm, bn, bk, wm, wn) in [(128, 64, 16, 2, 2), (64, 64, 8, 2, 2), (256, 128, 32, 4, 2)]:
+        for split in (2, 3, 4, 6, 8, 9, 12, 16):
+            for remap in (0, 1):
+                c = B.make_config(bm, bn, bk, wm, wn, split, remap)
+                if not B.config_legal(desc, c):
+                    continue
+                print(c, flush=True)
+                y = PT.run_gpu(RAGGED, x, w, cfg=c)
+                PT.assert_close(y, y_ref, d_ref, repr(c))
+
+
+SWEEP = [
+    # name, n, c, hw, k, rs, stride, pad, dil
+    ("s2", 2, 5, (17, 15), 9, 3, 2, 1, 1),
+    ("s3_pad0", 1, 7, (20, 22), 33, 3, 3, 0, 1),
+    ("dil2", 2, 6, (16, 18), 10, 3, 1, 2, 2),
+    ("dil_mixed", 1, 4, (15, 21), 6, (3, 2), (1, 2), (2, 1), (2, 3)),
+    ("rect_filter", 1, 3, (12, 30), 17, (5, 3), 1, (2, 1), 1),
+    ("seven", 2, 3, (30, 30), 16, 7, 2, 3, 1),
+    ("one_by_one", 3, 37, (9, 11), 70, 1, 1, 0, 1),
+    ("one_by_one_s2", 2, 40, (13, 13), 20, 1, 2, 0, 1),
+    ("pad_gt_half", 1, 3, (6, 6), 4, 3, 1, 3, 1),          # outer ring of outputs has no in-image tap
+    ("full_window", 4, 8, (5, 6), 12, (5, 6), 1, 0, 1),   # one output pixel per image
+    ("single", 1, 1, (1, 1), 1, 1, 1, 0, 1),
+    ("k1_c1", 1, 1, (40, 40), 1, 3, 1, 1, 1),
+    ("wide_k", 1, 8, (6, 6), 300, 3, 1, 1, 1),
+    ("long_reduction", 1, 520, (5, 5), 8, 3, 1, 1, 1),
+    ("table1_like", 1, 3, (28, 24), 16, 3, 1, 0, 1),
+]
+
+
+@pytest.mark.parametrize("row", SWEEP, ids=[r[0] for r in SWEEP])
+def test_shape_sweep_default_and_fixed_configs(row):
+    name, n, c, hw, k, rs, st, pd, dl = row
+    l = W.layer(name, n, c, hw, k, rs, st, pd, dl, x_dist="u11", w_dist="u11", seed=hash(name) % 1000)
+    desc = B.make_desc(l)
+    x, w = W.make_inputs(l)
+    y_ref, d_ref = PT.oracle_full(l, x, w)
+    print(name, "ref", flush=True)
+    PT.assert_close(PT.run_gpu(l, x, w, mode="ref"), y_ref, d_ref, name + " ref")
+    print(name, "default", B.config_default(desc), flush=True)
+    PT.assert_close(PT.run_gpu(l, x, w), y_ref, d_ref, name + " default")
+    for c_ in [B.make_config(64, 32, 8, 2, 1), B.make_config(128, 128, 16, 2, 2),
+               B.make_config(256, 64, 32, 4, 1), B.make_config(128, 64, 16, 4, 2, 2, 0)]:
+        if B.config_legal(desc, c_):
+            print(name, c_, flush=True)
+            PT.assert_close(PT.run_gpu(l, x, w, cfg=c_), y_ref, d_ref, name + repr(c_))
+
+
+def test_too_many_taps_uses_the_direct_kernel():
+    l = W.layer("taps64", 1, 2, (12, 12), 3, 8, 1, 2, 1, x_dist="u11", w_dist="u11", seed=5)
+    assert B.legal_configs(B.make_desc(l)) == []
+    PT.check_layer(l)
+
+
+def test_illegal_config_is_refused_before_launch():
+    torch, dev = PT.torch_dev()
+    desc = B.make_desc(RAGGED)
+    t = torch.zeros(16, device=dev)
+    rc = B.lib().wpk_conv2d_fwd_config(ctypes.byref(desc), ctypes.byref(B.make_config(128, 64, 16, 1, 1)),
+                                       ctypes.c_void_p(t.data_ptr()), ctypes.c_void_p(t.data_ptr()),
+                                       ctypes.c_void_p(t.data_ptr()), None)
+    assert rc == B.E_NO_CONFIG
+
+
+@pytest.mark.parametrize("layer", W.config3() + W.config4(), ids=lambda l: l["name"])
+def test_full_size_configs_3_and_4(layer):
+    """Full BASELINE sizes (N=16), whole output tensor against the oracle."""
+    print(layer["name"], B.config_default(B.make_desc(layer)), flush=True)
+    PT.check_layer(layer)
+
+
+def test_non_default_stream():
+    torch, dev = PT.torch_dev()
+    l = W.config2()[0]
+    desc = B.make_desc(l)
+    x, w = W.make_inputs(l)
+    y_ref, d_ref = PT.oracle_full(l, x, w)
+    xd, wd = PT.to_dev(x), PT.to_dev(w)
+    yd = torch.empty(y_ref.shape, device=dev, dtype=torch.float32)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        B.conv2d_fwd(desc, xd, wd, yd, stream=s)
+    s.synchronize()
+    PT.assert_close(yd.cpu().numpy(), y_ref, d_ref, "side stream")
