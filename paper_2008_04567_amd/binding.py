@@ -81,6 +81,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libwpk.so is missing: build it with "
                                "`python -m paper_2008_04567_amd.build` (no CPU fallback exists)")
+        try:                      # share PyTorch's HIP runtime: load it before the library
+            import torch          # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         P, I, V, D = ctypes.POINTER, ctypes.c_int, ctypes.c_void_p, ctypes.c_double
         i32p = P(ctypes.c_int32)

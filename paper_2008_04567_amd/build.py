@@ -65,8 +65,37 @@ def build_library(force=True, verbose=False):
             if verbose and out.strip():
                 print(out)
     objs = [j[-1] for j in jobs]
-    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+    _run(_link_command(objs))
     return LIB
+
+
+def _link_command(objs):
+    """Link against the HIP runtime PyTorch ships, when there is one.
+
+    The PyTorch-ROCm wheel bundles its own libamdhip64.so (file name without version, no
+    SONAME).  A process must hold ONE HIP runtime: tensors and streams made by PyTorch are
+    handed to this library.  Linking against the bundled file records the dependency under the
+    same name PyTorch uses, so whichever of the two is loaded first, the loader reuses it for
+    the other.  Without PyTorch the system runtime under /opt/rocm is used.
+    """
+    rocm_lib = "/opt/rocm/lib"
+    torch_lib = None
+    try:
+        import importlib.util
+        spec = importlib.util.find_spec("torch")
+        if spec and spec.origin:
+            cand = os.path.join(os.path.dirname(spec.origin), "lib")
+            if os.path.exists(os.path.join(cand, "libamdhip64.so")):
+                torch_lib = cand
+    except Exception:
+        torch_lib = None
+    cmd = ["g++", "-shared", "-fPIC", "-o", LIB] + objs
+    if torch_lib:
+        cmd += ["-L" + torch_lib, "-l:libamdhip64.so",
+                "-Wl,-rpath," + torch_lib + ":" + rocm_lib]
+    else:
+        cmd += ["-L" + rocm_lib, "-lamdhip64", "-Wl,-rpath," + rocm_lib]
+    return cmd
 
 
 if __name__ == "__main__":
