@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the forward-convolution hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: every layer of the
+workload once, through a plan (weights pre-packed at plan time, per-layer tuned configs),
+inputs and weights resident in HBM before the timed region.  Default workload: the four batched
+3x3 layers (N=16) the throughput target is quoted on.  Prints ONE JSON line on stdout; details
+go to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+FP32_MFMA_PEAK_TFLOPS = 157.3   # 256 CUs x 256 FLOP/clk x 2.4 GHz
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def workload_layers(W, name):
+    if name == "config3":
+        return W.config3(), "config3: four 3x3 s1 p1 layers, N=16, C=K in (64@56, 128@28, 256@14, 512@7)"
+    if name == "config4":
+        return W.config4(), "config4: pointwise and strided layers, N=16"
+    if name == "config2":
+        return W.config2(), "config2: 3x3 C=K=64 @56 and the 7x7/2 stem, N=1"
+    if name == "config1":
+        return W.config1(), "config1: N=1 C=K=16 14x14 3x3"
+    if name == "resnet50_n1":
+        return W.resnet50_stack(1), "config5: ResNet-50 conv stack (53 layers), N=1"
+    if name == "resnet50_n16":
+        return W.resnet50_stack(16), "config5: ResNet-50 conv stack (53 layers), N=16"
+    if name == "table1":
+        return W.table1_convs(), "Table 1 production layers, N=1"
+    raise SystemExit("unknown workload " + name)
+
+
+def cpu_baseline(W, layers, max_seconds=25.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the workload."""
+    from oracle import conv as oc
+    flops, secs, used, done = 0.0, 0.0, 1, []
+    for l in layers:
+        x, w = W.make_inputs(l)
+        sh = oc.shape_from_layer(l)
+        t0 = time.perf_counter()
+        y, _, used = oc.conv2d(sh, x, w, threads=0)
+        dt = time.perf_counter() - t0
+        P, Q = y.shape[2], y.shape[3]
+        flops += 2.0 * l["n"] * l["k"] * P * Q * l["c"] * l["r"] * l["s"]
+        secs += dt
+        done.append(l["name"])
+        if secs > max_seconds:
+            break
+    return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": int(used), "kind": "oracle",
+            "sample": "%d of %d layers, full batch, fp64 seven-loop, %.1f s wall: %s"
+                      % (len(done), len(layers), secs, ",".join(done))}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="config3")
+    ap.add_argument("--no-tune", action="store_true", help="use the untuned default configs")
+    ap.add_argument("--cache", default=None, help="search-result cache file to load/save")
+    ap.add_argument("--tune-mode", type=int, default=0, help="0 genetic, 1 random, 2 exhaustive")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--verbose-tune", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (--gpus 1)")
+
+    import numpy as np
+    import torch
+    from paper_2008_04567_amd import binding as B
+    from paper_2008_04567_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    dev_name, cus = B.device_info()
+    layers, wl_text = workload_layers(W, args.workload)
+    descs = [B.make_desc(l) for l in layers]
+    log("device %s, %d CUs; workload %s" % (dev_name, cus, wl_text))
+
+    if args.cache and os.path.exists(args.cache):
+        log("loaded %d cached search results" % B.cache_load(args.cache))
+    t_tune = time.perf_counter()
+    if not args.no_tune:
+        opt = B.tune_default_options(mode=args.tune_mode, verbose=1 if args.verbose_tune else 0)
+        seen = set()
+        for l, d in zip(layers, descs):
+            key = W.shape_key(l)
+            if key in seen:
+                continue
+            seen.add(key)
+            hit = B.cache_lookup(d) is not None
+            cid, rep = B.conv_tune_ex(d, opt, force=False)
+            if not hit:
+                log("tuned %-28s %-28s split %2d remap %d: %8.2f us (default %8.2f us), %d evals, "
+                    "%d gens, %.1f s" % (l["name"], B.config_kernel_name(rep.best), rep.best.split_k,
+                                         rep.best.xcd_remap, rep.best_us, rep.default_us,
+                                         rep.evaluations, rep.generations, rep.seconds))
+        if args.cache:
+            B.cache_save(args.cache)
+    t_tune = time.perf_counter() - t_tune
+
+    plan = B.Plan(descs, tune=False)
+    xs, ys, flops = [], [], []
+    for i, (l, d) in enumerate(zip(layers, descs)):
+        x, w = W.make_inputs(l)
+        P, Q = B.conv_out_shape(d)
+        xs.append(torch.from_numpy(x).to(dev))
+        wd = torch.from_numpy(w).to(dev)
+        ys.append(torch.empty((l["n"], l["k"], P, Q), device=dev, dtype=torch.float32))
+        plan.set_weights(i, wd)
+        flops.append(B.conv_flops(d))
+    xa, ya = plan.pointer_arrays(xs, ys)
+    stream = torch.cuda.current_stream()
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        plan.run(xa, ya, stream)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` passes, bracketed by synchronisation -----------------
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        plan.run(xa, ya, stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    total_flops = float(sum(flops))
+    value = total_flops / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-layer durations with events on the launch stream (same steps count) -------------
+    n = len(layers)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(n + 1)] for _ in range(args.steps)]
+    for s in range(args.steps):
+        ev[s][0].record(stream)
+        for i in range(n):
+            plan.run_layer(i, xs[i], ys[i], stream)
+            ev[s][i + 1].record(stream)
+    torch.cuda.synchronize()
+    per_layer_us = [1e3 * float(np.mean([ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(args.steps)]))
+                    for i in range(n)]
+    rows = []
+    for i, l in enumerate(layers):
+        cfg = plan.layer_config(i)
+        tf = flops[i] / (per_layer_us[i] * 1e-6) / 1e12
+        d = descs[i]
+        P, Q = B.conv_out_shape(d)
+        abytes = 4.0 * (l["n"] * l["c"] * l["h"] * l["w"] + l["k"] * l["c"] * l["r"] * l["s"]
+                        + l["n"] * l["k"] * P * Q)
+        rows.append({"layer": l["name"], "kernel": B.config_kernel_name(cfg), "split_k": cfg.split_k,
+                     "xcd_remap": cfg.xcd_remap, "us": round(per_layer_us[i], 2),
+                     "tflops": round(tf, 2), "pct_fp32_mfma_peak": round(100 * tf / FP32_MFMA_PEAK_TFLOPS, 1),
+                     "gbs_algorithmic": round(abytes / (per_layer_us[i] * 1e-6) / 1e9, 1)})
+        log("%-28s %-26s split %2d  %9.2f us  %7.2f TFLOP/s  %5.1f%% of fp32 MFMA peak  %7.1f GB/s"
+            % (l["name"], rows[-1]["kernel"], cfg.split_k, per_layer_us[i], tf,
+               rows[-1]["pct_fp32_mfma_peak"], rows[-1]["gbs_algorithmic"]))
+    dom = int(np.argmax(per_layer_us))
+    dom_tf = flops[dom] / (per_layer_us[dom] * 1e-6) / 1e12
+    roofline = {"bound": "mfma", "achieved": round(dom_tf, 3), "peak": FP32_MFMA_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(dom_tf / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                "kernel": rows[dom]["kernel"], "layer": rows[dom]["layer"],
+                "flops_per_launch": flops[dom], "avg_us": round(per_layer_us[dom], 2)}
+
+    out = {"metric": "conv2d fwd TFLOP/s (fp32, direct-convolution FLOP count) over the layer set",
+           "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": wl_text, "layers": n, "tuned": not args.no_tune,
+                      "tune_seconds": round(t_tune, 1)},
+           "pct_fp32_mfma_peak": round(100 * value / FP32_MFMA_PEAK_TFLOPS, 2),
+           "roofline": roofline, "layers": rows}
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(W, layers)
+    plan.destroy()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

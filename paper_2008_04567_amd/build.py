@@ -32,7 +32,10 @@ def _run(cmd):
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
-        raise RuntimeError("build step failed: %s\n%s" % (" ".join(cmd), out))
+        lines = out.splitlines()
+        if len(lines) > 60:
+            lines = lines[:60] + ["... (%d more lines)" % (len(lines) - 60)]
+        raise RuntimeError("build step failed: %s\n%s" % (" ".join(cmd), "\n".join(lines)))
     return out
 
 

@@ -397,6 +397,9 @@ static double tune_fitness(const int32_t *genes, int32_t n, void *user)
         return 0.0;
     }
     t->times_us[wpk_config_id(&cfg)] = us;
+    if (t->opt.verbose >= 2)
+        fprintf(stderr, "[wpk tune] %-28s split %2d remap %d: %9.2f us\n", wpk_config_kernel_name(&cfg),
+                cfg.split_k, cfg.xcd_remap, us);
     return 1.0 / us;
 }
 

@@ -18,11 +18,18 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+#include <utility>
+
 #include "wpk_internal.h"
 
 namespace wpk {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// Lambdas in the kernel must be inlined before the register arrays they capture are split up.
+#define WPK_LAMBDA __attribute__((always_inline))
 
 // Contiguous tile ranges per XCD: workgroup ids are dealt round-robin to the 8 XCDs, so id b runs
 // on XCD b%8; this maps it to a tile index such that each XCD owns one contiguous range.
@@ -32,6 +39,23 @@ __device__ __forceinline__ int xcd_remap(int bid, int nblocks)
     int xcd = bid % kNumXcd, idx = bid / kNumXcd;
     return xcd * per + (xcd < rem ? xcd : rem) + idx;
 }
+
+// Compile-time loop: every array index in the kernel is a constant at the source level, so the
+// register arrays below are split into scalars by the first optimisation passes and never end up
+// in scratch or LDS.
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// The tap table is read through the constant address space: wave-uniform scalar loads.
+typedef const int __attribute__((address_space(4))) *tap_ptr;
 
 template <int BM, int BN, int BK, int WM, int WN>
 __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
@@ -70,8 +94,8 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     const int rg = __builtin_amdgcn_readfirstlane(tid / BM);  // 0 when T <= BM
     int xbase[XP];
     unsigned long long tapmask[XP];
-#pragma unroll
-    for (int i = 0; i < XP; ++i) {
+    static_for<XP>([&](auto I) WPK_LAMBDA {
+        constexpr int i = decltype(I)::value;
         int m = m0 + pm0 + i * T;
         xbase[i] = 0;
         tapmask[i] = 0;
@@ -91,112 +115,145 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
             }
             tapmask[i] = msk;
         }
-    }
+    });
     const __amdgpu_buffer_rsrc_t xrsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)a.x_bytes, 0x00020000);
+    const tap_ptr taps = (tap_ptr)(unsigned long long)a.ktab;
+    const float *wsrc = a.wp + n0;
 
-    float xr[XP][XR];
-    float4 wr[WL];
+    float xr[XP * XR];
+    v4f wr[WL];
 
-    auto gload = [&](int step) {
+    // A row group owns XR consecutive reduction rows of the step, so its tap-table entries are
+    // one contiguous, wave-uniform block: fetched with scalar loads, all before the first use.
+    auto gload = [&](int step) WPK_LAMBDA {
         const int k0 = step * BK;
-#pragma unroll
-        for (int jj = 0; jj < XR; ++jj) {
-            const int row = k0 + rg + RG * jj;
-            const int delta = a.ktab[2 * row];
-            const int tap = a.ktab[2 * row + 1];
-#pragma unroll
-            for (int i = 0; i < XP; ++i) {
-                bool valid = (tapmask[i] >> tap) & 1ull;
-                unsigned off = valid ? (unsigned)(xbase[i] + delta) * 4u : 0x80000000u;
-                xr[i][jj] = __builtin_bit_cast(
+        tap_ptr tp = taps + 2 * (k0 + rg * XR);
+        int tap_off[XR], tap_idx[XR];
+        static_for<XR>([&](auto J) WPK_LAMBDA {
+            tap_off[decltype(J)::value] = tp[2 * decltype(J)::value];
+            tap_idx[decltype(J)::value] = tp[2 * decltype(J)::value + 1];
+        });
+        static_for<XR>([&](auto J) WPK_LAMBDA {
+            constexpr int jj = decltype(J)::value;
+            static_for<XP>([&](auto I) WPK_LAMBDA {
+                constexpr int i = decltype(I)::value;
+                unsigned bit = (unsigned)(tapmask[i] >> tap_idx[jj]) & 1u;
+                unsigned off = bit ? (unsigned)(xbase[i] + tap_off[jj]) * 4u : 0x80000000u;
+                xr[i * XR + jj] = __builtin_bit_cast(
                     float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, (int)off, 0, 0));
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < WL; ++i) {
+            });
+        });
+        static_for<WL>([&](auto I) WPK_LAMBDA {
+            constexpr int i = decltype(I)::value;
             int e = tid + i * T;
             if (W4 % T == 0 || e < W4) {
                 int row = e / (BN / 4), c4 = e % (BN / 4);
-                wr[i] = *reinterpret_cast<const float4 *>(a.wp + (size_t)(k0 + row) * a.Kpad + n0 + c4 * 4);
+                wr[i] = *reinterpret_cast<const v4f *>(wsrc + (size_t)(k0 + row) * a.Kpad + c4 * 4);
             }
-        }
+        });
     };
-    auto lstore = [&](int buf) {
-#pragma unroll
-        for (int jj = 0; jj < XR; ++jj)
-#pragma unroll
-            for (int i = 0; i < XP; ++i) Xs[buf][(rg + RG * jj) * BM + pm0 + i * T] = xr[i][jj];
-#pragma unroll
-        for (int i = 0; i < WL; ++i) {
+    auto lstore = [&](int buf) WPK_LAMBDA {
+        static_for<XR>([&](auto J) WPK_LAMBDA {
+            constexpr int jj = decltype(J)::value;
+            static_for<XP>([&](auto I) WPK_LAMBDA {
+                constexpr int i = decltype(I)::value;
+                Xs[buf][(rg * XR + jj) * BM + pm0 + i * T] = xr[i * XR + jj];
+            });
+        });
+        static_for<WL>([&](auto I) WPK_LAMBDA {
+            constexpr int i = decltype(I)::value;
             int e = tid + i * T;
-            if (W4 % T == 0 || e < W4) *reinterpret_cast<float4 *>(&Ws[buf][e * 4]) = wr[i];
-        }
+            if (W4 % T == 0 || e < W4) *reinterpret_cast<v4f *>(&Ws[buf][e * 4]) = wr[i];
+        });
     };
 
-    v16f acc[NNT][NMT];
-#pragma unroll
-    for (int i = 0; i < NNT; ++i)
-#pragma unroll
-        for (int j = 0; j < NMT; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    v16f acc[NNT * NMT];
+    static_for<NNT * NMT>([&](auto I) WPK_LAMBDA {
+        static_for<16>([&](auto E) WPK_LAMBDA { acc[decltype(I)::value][decltype(E)::value] = 0.0f; });
+    });
 
     const int kbeg = split * a.steps_per_split;
     const int kend = min(a.nsteps, kbeg + a.steps_per_split);
     const int lrow = lane >> 5, lcol = lane & 31;
 
+    // Three-deep pipeline over two LDS buffers: while the MFMAs of step s read buffer s&1, the
+    // tile of step s+1 (in registers since the previous step) is stored to the other buffer and
+    // the global loads of step s+2 are issued.  One barrier per step, at its end.
     if (kbeg < kend) {
         gload(kbeg);
         lstore(0);
+        if (kbeg + 1 < kend) gload(kbeg + 1);
     }
     __syncthreads();
+    // LDS read instructions per row pair after the compiler pairs neighbouring 32-column blocks
+    constexpr int DSR = (NNT + 1) / 2 + (NMT + 1) / 2;
     for (int step = kbeg; step < kend; ++step) {
         const int cur = (step - kbeg) & 1;
-        const bool more = step + 1 < kend;
-        if (more) gload(step + 1);
-        const float *xs = Xs[cur] + wave_m * TM + lcol;
-        const float *ws = Ws[cur] + wave_n * TN + lcol;
-#pragma unroll
-        for (int kk = 0; kk < BK; kk += 2) {
-            float av[NNT], bv[NMT];
-#pragma unroll
-            for (int i = 0; i < NNT; ++i) av[i] = ws[(kk + lrow) * BN + i * 32];
-#pragma unroll
-            for (int j = 0; j < NMT; ++j) bv[j] = xs[(kk + lrow) * BM + j * 32];
-#pragma unroll
-            for (int i = 0; i < NNT; ++i)
-#pragma unroll
-                for (int j = 0; j < NMT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
-        }
-        if (more) lstore(cur ^ 1);
+        const float *xs = Xs[cur] + wave_m * TM + lcol + lrow * BM;
+        const float *ws = Ws[cur] + wave_n * TN + lcol + lrow * BN;
+        // operands of row pair kk+2 are fetched from LDS before the MFMAs of row pair kk issue
+        float av[2 * NNT], bv[2 * NMT];
+        static_for<NNT>([&](auto I) WPK_LAMBDA { av[decltype(I)::value] = ws[decltype(I)::value * 32]; });
+        static_for<NMT>([&](auto J) WPK_LAMBDA { bv[decltype(J)::value] = xs[decltype(J)::value * 32]; });
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        if (step + 1 < kend) lstore(cur ^ 1);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        if (step + 2 < kend) gload(step + 2);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<BK / 2>([&](auto KK) WPK_LAMBDA {
+            constexpr int kk = decltype(KK)::value * 2;
+            constexpr int c = (kk >> 1) & 1, nx = c ^ 1;
+            if constexpr (kk + 2 < BK) {
+                static_for<NNT>([&](auto I) WPK_LAMBDA {
+                    av[nx * NNT + decltype(I)::value] = ws[(kk + 2) * BN + decltype(I)::value * 32];
+                });
+                static_for<NMT>([&](auto J) WPK_LAMBDA {
+                    bv[nx * NMT + decltype(J)::value] = xs[(kk + 2) * BM + decltype(J)::value * 32];
+                });
+                __builtin_amdgcn_sched_group_barrier(0x100, DSR, 0);
+            }
+            static_for<NNT>([&](auto I) WPK_LAMBDA {
+                static_for<NMT>([&](auto J) WPK_LAMBDA {
+                    constexpr int i = decltype(I)::value, j = decltype(J)::value;
+                    acc[i * NMT + j] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                        av[c * NNT + i], bv[c * NMT + j], acc[i * NMT + j], 0, 0, 0);
+                });
+            });
+            __builtin_amdgcn_sched_group_barrier(0x008, NNT * NMT, 0);
+        });
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
     }
 
     // ---- epilogue: D[row = channel][col = pixel]; register e of lane l holds row
     //      8*(e/4) + 4*(l/32) + e%4 and column l%32 of its 32x32 block ---------------------------
-#pragma unroll
-    for (int j = 0; j < NMT; ++j) {
+    const bool atomic = a.split_k > 1;
+    static_for<NMT>([&](auto J) WPK_LAMBDA {
+        constexpr int j = decltype(J)::value;
         int m = m0 + wave_m * TM + j * 32 + lcol;
-        if (m >= a.M) continue;
-        int n = m / a.PQ, pq = m - n * a.PQ;
-        float *yp = a.y + (size_t)n * a.K * a.PQ + pq;
-#pragma unroll
-        for (int i = 0; i < NNT; ++i) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                int kout = n0 + wave_n * TN + i * 32 + 8 * (e / 4) + 4 * lrow + (e & 3);
-                if (kout < a.K) {
-                    float *dst = yp + (size_t)kout * a.PQ;
-                    if (a.split_k > 1)
-                        unsafeAtomicAdd(dst, acc[i][j][e]);
-                    else
-                        *dst = acc[i][j][e];
-                }
-            }
+        if (m < a.M) {
+            int n = m / a.PQ, pq = m - n * a.PQ;
+            float *yp = a.y + (size_t)n * a.K * a.PQ + pq;
+            static_for<NNT>([&](auto I) WPK_LAMBDA {
+                constexpr int i = decltype(I)::value;
+                static_for<16>([&](auto E) WPK_LAMBDA {
+                    constexpr int e = decltype(E)::value;
+                    int kout = n0 + wave_n * TN + i * 32 + 8 * (e / 4) + 4 * lrow + (e & 3);
+                    if (kout < a.K) {
+                        float *dst = yp + (size_t)kout * a.PQ;
+                        if (atomic)
+                            unsafeAtomicAdd(dst, acc[i * NMT + j][e]);
+                        else
+                            *dst = acc[i * NMT + j][e];
+                    }
+                });
+            });
         }
-    }
+    });
 }
 
 template <int BM, int BN, int BK, int WM, int WN>
