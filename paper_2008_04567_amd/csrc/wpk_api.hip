@@ -38,7 +38,8 @@ static const LaunchFn kLaunch[] = {
 #undef WPK_VARIANT
 
 // ---- helper kernels ---------------------------------------------------------------------------------
-// w[K][CRS] -> wp[CRSpad][Kpad], zero padded, through a 32x32 LDS tile so both sides coalesce.
+// w[K][CRS] -> wp[CRSpad/4][Kpad][4] (element (kk, k) at ((kk/4)*Kpad + k)*4 + kk%4), zero padded,
+// through a 32x32 LDS tile so both sides coalesce.
 __global__ void __launch_bounds__(256) pack_weights_kernel(const float *__restrict__ w,
                                                            float *__restrict__ wp, int K, int CRS,
                                                            int Kpad)
@@ -52,11 +53,10 @@ __global__ void __launch_bounds__(256) pack_weights_kernel(const float *__restri
         tile[ty + i * 8][tx] = (k < K && kk < CRS) ? w[(size_t)k * CRS + kk] : 0.0f;
     }
     __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int kk = kk0 + ty + i * 8, k = k0 + tx;
-        wp[(size_t)kk * Kpad + k] = tile[tx][ty + i * 8];
-    }
+    // a thread writes one quad: channel k0 + (t % 32), k quad kk0/4 + t/32
+    const int kq = threadIdx.x >> 5, kc = threadIdx.x & 31;
+    float4 v = make_float4(tile[kc][4 * kq], tile[kc][4 * kq + 1], tile[kc][4 * kq + 2], tile[kc][4 * kq + 3]);
+    *reinterpret_cast<float4 *>(wp + ((size_t)(kk0 / 4 + kq) * Kpad + k0 + kc) * 4) = v;
 }
 
 // One output element per lane, the three reduction loops written out; 64-bit indexing.
@@ -147,20 +147,25 @@ static int ensure_device()
     return WPK_OK;
 }
 
-// Tap table of a problem: for reduction row kk = (c*R + r)*S + s the element offset of the tap
-// inside one image, c*H*W + r*dil_h*W + s*dil_w, and the tap number r*S+s; padding rows get 63.
+// Tap table of a problem, four ints per reduction row kk = (c*R + r)*S + s: the byte offset of the
+// tap inside one image relative to the window origin, (c*H*W + (r*dil_h - pad_h)*W + s*dil_w - pad_w)*4,
+// plus the bias (pad_h*W + pad_w)*4 that makes it non-negative; the mask bit of filter row r; the
+// mask bit of filter column s (16 + s); zero.  Padding rows point at the always-set bit 31.
 static std::vector<int32_t> build_tap_table(const Problem &pr)
 {
     const wpk_conv_desc &d = pr.d;
-    std::vector<int32_t> t((size_t)pr.CRSpad * 2);
+    std::vector<int32_t> t((size_t)pr.CRSpad * 4, 0);
+    const int bias = (d.pad_h * d.w + d.pad_w) * 4;
     for (int kk = 0; kk < pr.CRSpad; ++kk) {
         if (kk < pr.CRS) {
             int s = kk % d.s, r = (kk / d.s) % d.r, c = kk / (d.s * d.r);
-            t[2 * kk] = c * d.h * d.w + r * d.dil_h * d.w + s * d.dil_w;
-            t[2 * kk + 1] = r * d.s + s;
+            t[4 * kk] = (c * d.h * d.w + (r * d.dil_h - d.pad_h) * d.w + s * d.dil_w - d.pad_w) * 4 + bias;
+            t[4 * kk + 1] = r;
+            t[4 * kk + 2] = 16 + s;
         } else {
-            t[2 * kk] = 0;
-            t[2 * kk + 1] = kMaxTaps;
+            t[4 * kk] = 0;
+            t[4 * kk + 1] = kPadTapBit;
+            t[4 * kk + 2] = kPadTapBit;
         }
     }
     return t;
@@ -238,6 +243,8 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     a.tiles_n = (d.k + cfg.bn - 1) / cfg.bn;
     a.remap = cfg.xcd_remap;
     a.x_bytes = (uint32_t)(pr.x_elems * 4);
+    a.x_bias = (uint32_t)((d.pad_h * d.w + d.pad_w) * 4);
+    a.w_bytes = (uint32_t)((int64_t)pr.CRSpad * pr.Kpad * 4);
     if (cfg.split_k > 1) {
         int rc = zero_fill(y, pr.y_elems, st);
         if (rc != WPK_OK) return rc;

@@ -97,7 +97,9 @@ int make_problem(const wpk_conv_desc *d, Problem *out)
     pr.CRS = (int32_t)crs;
     pr.CRSpad = (int32_t)((crs + kRedAlign - 1) / kRedAlign * kRedAlign);
     pr.Kpad = (d->k + kKoutAlign - 1) / kKoutAlign * kKoutAlign;
-    pr.tiled_ok = d->r * d->s <= kMaxTaps && pr.x_elems * 4 <= kMaxTiledBytes &&
+    int64_t bias = ((int64_t)d->pad_h * d->w + d->pad_w) * 4;
+    pr.tiled_ok = d->r <= kMaxFilterRows && d->s <= kMaxFilterCols &&
+                  pr.x_elems * 4 + bias <= kMaxTiledBytes &&
                   pr.y_elems * 4 <= kMaxTiledBytes && (int64_t)pr.CRSpad * pr.Kpad * 4 <= kMaxTiledBytes;
     *out = pr;
     return WPK_OK;
@@ -136,8 +138,10 @@ bool legal_for(const Problem &pr, const wpk_conv_config &cfg)
         if (value_index(g, f[g]) < 0) return false;
     if (!pr.tiled_ok) return false;
     if (find_variant(cfg.bm, cfg.bn, cfg.bk, cfg.wm, cfg.wn) < 0) return false;
-    if (64 * cfg.wm * cfg.wn > 1024) return false;                       // workgroup size
-    if (2 * cfg.bk * (cfg.bm + cfg.bn) * 4 > kMaxLdsBytes) return false;  // two LDS stages
+    int threads = 64 * cfg.wm * cfg.wn;
+    if (threads > 1024) return false;                                             // workgroup size
+    if (2 * (cfg.bk + 4) * (cfg.bm + cfg.bn) * 4 > kMaxLdsBytes) return false;    // two LDS stages
+    if (threads > cfg.bm && (cfg.bk * cfg.bm / threads) % 4 != 0) return false;   // whole k quads per thread
     int32_t nsteps = (pr.CRS + cfg.bk - 1) / cfg.bk;
     if (cfg.split_k > nsteps) return false;
     int64_t tiles = ((pr.M + cfg.bm - 1) / cfg.bm) * ((pr.d.k + cfg.bn - 1) / cfg.bn);

@@ -1,18 +1,30 @@
 // The tiled implicit-GEMM forward convolution kernel family for gfx950 (CDNA4, wave64).
 //
-// GEMM view that matches NCHW memory: Y[kout][pixel] = sum_kk Wp[kk][kout] * Xcol[kk][pixel],
+// GEMM view that matches NCHW memory: Y[kout][pixel] = sum_kk W[kout][kk] * Xcol[kk][pixel],
 // pixel = (n,p,q) flattened, kk = (c,r,s) flattened in the weights' own KCRS order.  x and y are
-// both contiguous along q, so activation loads and output stores coalesce along the pixel axis;
-// the weights are re-packed once into reduction-major [CRSpad][Kpad] so a weight tile is a plain
-// 16-byte-per-lane stream.  The im2col matrix is never written to memory: a workgroup gathers a
-// BK x BM activation tile per step straight into LDS.  A per-problem tap table gives, for every
-// reduction row, the element offset of its tap inside x and its tap number r*S+s; each lane keeps
-// a 64-bit mask of the taps that fall inside the image for its pixel, and out-of-image taps are
-// loaded through a buffer descriptor at an out-of-range offset, which returns zero.
+// both contiguous along q, so activation loads and output stores coalesce along the pixel axis.
+// The im2col matrix is never written to memory: per reduction step a workgroup gathers a
+// BK x BM activation tile and a BK x BN weight tile into LDS.
 //
-// The contraction runs on v_mfma_f32_32x32x2_f32: A = 32 output channels x 2 reduction rows,
-// B = 2 reduction rows x 32 pixels, D = 32 x 32 with the pixel index on the lane axis, so that
-// each accumulator register of a half-wave stores 32 consecutive pixels (128 contiguous bytes).
+// Gather.  A per-problem tap table gives, for every reduction row, the byte offset of its tap
+// inside one image and the filter row r / column s it belongs to.  Each lane owns one output
+// pixel: a constant byte offset of the pixel's window origin and a bit mask of the filter rows
+// and columns that fall outside the image for that pixel.  A load is then one buffer load with
+// the lane offset in the VGPR and the tap offset in the SGPR; out-of-image taps get an offset
+// of all ones, which the buffer range check turns into a zero.
+//
+// LDS layout.  Both tiles are stored reduction-contiguous: tile[column][k] with a row pitch of
+// BK+4 floats, so that a lane moves four consecutive k values of its column with one 16-byte LDS
+// access and the 16 lanes served per clock hit 16 distinct groups of four banks.  The weights
+// are pre-packed as [kk/4][kout][4] so that a 16-byte global load is exactly one such quad.
+//
+// Contraction.  v_mfma_f32_32x32x2_f32 multiplies A = 32 channels x 2 k by B = 2 k x 32 pixels.
+// Lanes 0-31 supply k index 0 and lanes 32-63 k index 1 of both operands, and any pairing of k
+// values is a valid contraction as long as A and B agree.  For eight consecutive k values the
+// low half-wave holds k0..k0+3 and the high half-wave k0+4..k0+7 of its column (one 16-byte LDS
+// read each); MFMA number q of four contracts the pair (k0+q, k0+4+q).  D = 32 x 32 has the pixel
+// index on the lane axis, so each accumulator register of a half-wave stores 32 consecutive
+// pixels (128 contiguous bytes of y).
 #ifndef WPK_IGEMM_H
 #define WPK_IGEMM_H
 
@@ -57,29 +69,37 @@ __device__ __forceinline__ void static_for(F &&f)
 // The tap table is read through the constant address space: wave-uniform scalar loads.
 typedef const int __attribute__((address_space(4))) *tap_ptr;
 
+// LDS row pitch (floats) of a reduction-contiguous tile with BK k values per column.
+__host__ __device__ constexpr int lds_pitch(int bk) { return bk + 4; }
+
 template <int BM, int BN, int BK, int WM, int WN>
 __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
 {
     constexpr int T = 64 * WM * WN;
-    constexpr int TM = BM / WM, TN = BN / WN;   // wave tile
-    constexpr int NMT = TM / 32, NNT = TN / 32; // 32x32 MFMA blocks per wave tile
-    constexpr int XP = BM > T ? BM / T : 1;     // pixels per thread in the gather
-    constexpr int RG = T > BM ? T / BM : 1;     // row groups in the gather
-    constexpr int XR = BK / RG;                 // rows per thread per pixel
-    constexpr int W4 = BK * BN / 4;             // float4s in a weight tile
-    constexpr int WL = (W4 + T - 1) / T;
+    constexpr int TM = BM / WM, TN = BN / WN;    // wave tile
+    constexpr int NMT = TM / 32, NNT = TN / 32;  // 32x32 MFMA blocks per wave tile
+    constexpr int XP = BM > T ? BM / T : 1;      // pixels per thread in the gather
+    constexpr int RG = T > BM ? T / BM : 1;      // row groups in the gather
+    constexpr int XR = BK / RG;                  // consecutive reduction rows per thread and pixel
+    constexpr int W4 = BK / 4 * BN;              // 16-byte quads in a weight tile
+    constexpr int WL = (W4 + T - 1) / T;         // quads per thread
+    constexpr int PX = lds_pitch(BK), PW = lds_pitch(BK);
+    constexpr int XTILE = BM * PX, WTILE = BN * PW;
     static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be whole MFMA blocks");
-    static_assert(BM % 64 == 0, "a wave gathers one reduction row at a time");
-    static_assert(BK % RG == 0 && BK % 2 == 0, "row groups must divide the step");
+    static_assert(BM % 64 == 0, "a wave gathers whole reduction rows");
+    static_assert(BK % 8 == 0, "the MFMA pairing works on octets of k");
+    static_assert(BK % RG == 0 && XR % 4 == 0, "a thread must own whole k quads");
     static_assert((T >= BM && T % BM == 0) || (T < BM && BM % T == 0), "gather mapping");
+    static_assert(T % BN == 0, "weight quads: every thread keeps one channel");
 
-    __shared__ float Xs[2][BK * BM];
-    __shared__ __attribute__((aligned(16))) float Ws[2][BK * BN];
+    __shared__ __attribute__((aligned(16))) float lds[2 * (XTILE + WTILE)];
+    float *const Xs0 = lds, *const Ws0 = lds + 2 * XTILE;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_m = wave % WM, wave_n = wave / WM;
+    const int lrow = lane >> 5, lcol = lane & 31;
 
     int bid = blockIdx.x;
     if (a.remap) bid = xcd_remap(bid, gridDim.x);
@@ -89,83 +109,94 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     const int split = t2 / a.tiles_m;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-    // ---- per-thread gather state: pixel offset inside x and the in-image tap mask ------------
+    // ---- per-thread gather state ---------------------------------------------------------------
+    // xvoff: byte offset of the pixel's window origin (before padding is subtracted; the padding
+    //        shift is folded into the tap offsets and the buffer base, so it is never negative);
+    // xinv : bit r set = filter row r is outside the image for this pixel, bit 16+s = column s;
+    //        bit 31 is always set and is what the table's padding rows point at.
     const int pm0 = tid % (T < BM ? T : BM);
     const int rg = __builtin_amdgcn_readfirstlane(tid / BM);  // 0 when T <= BM
-    int xbase[XP];
-    unsigned long long tapmask[XP];
+    int xvoff[XP];
+    unsigned xinv[XP];
     static_for<XP>([&](auto I) WPK_LAMBDA {
         constexpr int i = decltype(I)::value;
         int m = m0 + pm0 + i * T;
-        xbase[i] = 0;
-        tapmask[i] = 0;
+        xvoff[i] = 0;
+        xinv[i] = 0xffffffffu;
         if (m < a.M) {
             int n = m / a.PQ, pq = m - n * a.PQ;
             int p = pq / a.Q, q = pq - p * a.Q;
             int ih0 = p * a.stride_h - a.pad_h, iw0 = q * a.stride_w - a.pad_w;
-            xbase[i] = (n * a.C * a.H + ih0) * a.W + iw0;
-            unsigned long long msk = 0;
+            xvoff[i] = ((n * a.C * a.H + p * a.stride_h) * a.W + q * a.stride_w) * 4;
+            unsigned inv = 0x80000000u;
             for (int r = 0; r < a.R; ++r) {
                 int ih = ih0 + r * a.dil_h;
-                bool hin = ih >= 0 && ih < a.H;
-                for (int s = 0; s < a.S; ++s) {
-                    int iw = iw0 + s * a.dil_w;
-                    if (hin && iw >= 0 && iw < a.W) msk |= 1ull << (r * a.S + s);
-                }
+                if (ih < 0 || ih >= a.H) inv |= 1u << r;
             }
-            tapmask[i] = msk;
+            for (int sx = 0; sx < a.S; ++sx) {
+                int iw = iw0 + sx * a.dil_w;
+                if (iw < 0 || iw >= a.W) inv |= 1u << (16 + sx);
+            }
+            xinv[i] = inv;
         }
     });
-    const __amdgpu_buffer_rsrc_t xrsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)a.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)((const char *)a.x - a.x_bias), 0, (int)(a.x_bytes + a.x_bias), 0x00020000);
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.wp, 0, (int)a.w_bytes, 0x00020000);
     const tap_ptr taps = (tap_ptr)(unsigned long long)a.ktab;
-    const float *wsrc = a.wp + n0;
+    // weight quads: this thread's channel and first k quad inside the tile
+    const int wkout = tid % BN, wkq = tid / BN;
+    const int wvoff = (wkq * a.Kpad + n0 + wkout) * 16;
+    const int wstep_bytes = (BK / 4) * a.Kpad * 16;  // one reduction step further
+    const int wquad_bytes = (T / BN) * a.Kpad * 16;  // this thread's next quad in the same step
 
-    float xr[XP * XR];
-    v4f wr[WL];
+    // ---- staging registers: one tile (activations and weights) in flight between global memory
+    //      and LDS ---------------------------------------------------------------------------------
+    constexpr int NX = XP * XR;   // activation dwords per thread
+    constexpr int NXQ = NX / 4;   // ... stored to LDS as quads
+    constexpr int NW = WL;        // weight quads per thread
+    float xr[NX];
+    v4f wr[NW];
+    int tap_off[XR], tap_r[XR], tap_s[XR];  // wave-uniform: live in scalar registers
 
     // A row group owns XR consecutive reduction rows of the step, so its tap-table entries are
-    // one contiguous, wave-uniform block: fetched with scalar loads, all before the first use.
-    auto gload = [&](int step) WPK_LAMBDA {
-        const int k0 = step * BK;
-        tap_ptr tp = taps + 2 * (k0 + rg * XR);
-        int tap_off[XR], tap_idx[XR];
-        static_for<XR>([&](auto J) WPK_LAMBDA {
-            tap_off[decltype(J)::value] = tp[2 * decltype(J)::value];
-            tap_idx[decltype(J)::value] = tp[2 * decltype(J)::value + 1];
-        });
+    // one contiguous, wave-uniform block fetched with scalar loads.
+    auto load_taps = [&](int step) WPK_LAMBDA {
+        tap_ptr tp = taps + 4 * (step * BK + rg * XR);
         static_for<XR>([&](auto J) WPK_LAMBDA {
             constexpr int jj = decltype(J)::value;
-            static_for<XP>([&](auto I) WPK_LAMBDA {
-                constexpr int i = decltype(I)::value;
-                unsigned bit = (unsigned)(tapmask[i] >> tap_idx[jj]) & 1u;
-                unsigned off = bit ? (unsigned)(xbase[i] + tap_off[jj]) * 4u : 0x80000000u;
-                xr[i * XR + jj] = __builtin_bit_cast(
-                    float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, (int)off, 0, 0));
-            });
-        });
-        static_for<WL>([&](auto I) WPK_LAMBDA {
-            constexpr int i = decltype(I)::value;
-            int e = tid + i * T;
-            if (W4 % T == 0 || e < W4) {
-                int row = e / (BN / 4), c4 = e % (BN / 4);
-                wr[i] = *reinterpret_cast<const v4f *>(wsrc + (size_t)(k0 + row) * a.Kpad + c4 * 4);
-            }
+            tap_off[jj] = tp[4 * jj];
+            tap_r[jj] = tp[4 * jj + 1];
+            tap_s[jj] = tp[4 * jj + 2];
         });
     };
-    auto lstore = [&](int buf) WPK_LAMBDA {
-        static_for<XR>([&](auto J) WPK_LAMBDA {
-            constexpr int jj = decltype(J)::value;
-            static_for<XP>([&](auto I) WPK_LAMBDA {
-                constexpr int i = decltype(I)::value;
-                Xs[buf][(rg * XR + jj) * BM + pm0 + i * T] = xr[i * XR + jj];
-            });
-        });
-        static_for<WL>([&](auto I) WPK_LAMBDA {
-            constexpr int i = decltype(I)::value;
-            int e = tid + i * T;
-            if (W4 % T == 0 || e < W4) *reinterpret_cast<v4f *>(&Ws[buf][e * 4]) = wr[i];
-        });
+    // global -> register: activation dword E of the tile
+    auto load_x = [&](auto E) WPK_LAMBDA {
+        constexpr int e = decltype(E)::value, i = e / XR, jj = e % XR;
+        int bad = __builtin_amdgcn_sbfe((int)xinv[i], tap_r[jj], 1) |
+                  __builtin_amdgcn_sbfe((int)xinv[i], tap_s[jj], 1);  // 0 or all ones
+        xr[e] = __builtin_bit_cast(
+            float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, xvoff[i] | bad, tap_off[jj], 0));
+    };
+    // global -> register: weight quad E of the tile of `step`
+    auto load_w = [&](int step, auto E) WPK_LAMBDA {
+        constexpr int i = decltype(E)::value;
+        if (W4 % T == 0 || wkq + i * (T / BN) < BK / 4)
+            wr[i] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(
+                                                wrsrc, wvoff, step * wstep_bytes + i * wquad_bytes, 0));
+    };
+    // register -> LDS buffer `buf`
+    auto store_x = [&](int buf, auto E) WPK_LAMBDA {
+        constexpr int e = decltype(E)::value, i = e / (XR / 4), j4 = e % (XR / 4);
+        v4f v = {xr[i * XR + 4 * j4], xr[i * XR + 4 * j4 + 1], xr[i * XR + 4 * j4 + 2],
+                 xr[i * XR + 4 * j4 + 3]};
+        *reinterpret_cast<v4f *>(Xs0 + buf * XTILE + (pm0 + i * T) * PX + rg * XR + 4 * j4) = v;
+    };
+    auto store_w = [&](int buf, auto E) WPK_LAMBDA {
+        constexpr int i = decltype(E)::value;
+        if (W4 % T == 0 || wkq + i * (T / BN) < BK / 4)
+            *reinterpret_cast<v4f *>(Ws0 + buf * WTILE + wkout * PW + (wkq + i * (T / BN)) * 4) = wr[i];
     };
 
     v16f acc[NNT * NMT];
@@ -175,59 +206,93 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
 
     const int kbeg = split * a.steps_per_split;
     const int kend = min(a.nsteps, kbeg + a.steps_per_split);
-    const int lrow = lane >> 5, lcol = lane & 31;
 
-    // Three-deep pipeline over two LDS buffers: while the MFMAs of step s read buffer s&1, the
-    // tile of step s+1 (in registers since the previous step) is stored to the other buffer and
-    // the global loads of step s+2 are issued.  One barrier per step, at its end.
+    // One reduction step.  Three-deep pipeline over two LDS buffers: the MFMAs of step s read
+    // buffer s&1; meanwhile the tile of step s+1 (in the staging registers since the previous
+    // step) is stored to the other buffer (STORE) and then the tile of step s+2 is loaded from
+    // global memory into the same registers (LOAD).  These stores and loads are dealt out one by
+    // one behind the individual MFMAs, each of which keeps the matrix pipe busy for 64 cycles, so
+    // they issue in its shadow; the LDS operands of octet o+1 are read before the MFMAs of octet
+    // o.  One barrier per step, at its end.
+    constexpr int NM = (BK / 2) * NNT * NMT;       // MFMAs per step and wave
+    constexpr int NIT = NXQ + NW + NX + NW;        // stores (x, w) then loads (x, w)
+    auto step_body = [&](int step, auto STORE, auto LOAD) WPK_LAMBDA {
+        constexpr bool do_store = decltype(STORE)::value, do_load = decltype(LOAD)::value;
+        const int cur = (step - kbeg) & 1;
+        const float *xs = Xs0 + cur * XTILE + (wave_m * TM + lcol) * PX + lrow * 4;
+        const float *ws = Ws0 + cur * WTILE + (wave_n * TN + lcol) * PW + lrow * 4;
+        v4f av[2 * NNT], bv[2 * NMT];
+        static_for<NNT>([&](auto I) WPK_LAMBDA {
+            av[decltype(I)::value] = *reinterpret_cast<const v4f *>(ws + decltype(I)::value * 32 * PW);
+        });
+        static_for<NMT>([&](auto J) WPK_LAMBDA {
+            bv[decltype(J)::value] = *reinterpret_cast<const v4f *>(xs + decltype(J)::value * 32 * PX);
+        });
+        if constexpr (do_load) load_taps(step + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<BK / 8>([&](auto KO) WPK_LAMBDA {
+            constexpr int ko = decltype(KO)::value;
+            constexpr int c = ko & 1, nx = c ^ 1;
+            if constexpr (ko + 1 < BK / 8) {
+                static_for<NNT>([&](auto I) WPK_LAMBDA {
+                    av[nx * NNT + decltype(I)::value] = *reinterpret_cast<const v4f *>(
+                        ws + decltype(I)::value * 32 * PW + (ko + 1) * 8);
+                });
+                static_for<NMT>([&](auto J) WPK_LAMBDA {
+                    bv[nx * NMT + decltype(J)::value] = *reinterpret_cast<const v4f *>(
+                        xs + decltype(J)::value * 32 * PX + (ko + 1) * 8);
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            static_for<4 * NNT * NMT>([&](auto QIJ) WPK_LAMBDA {
+                constexpr int qij = decltype(QIJ)::value;
+                constexpr int q = qij / (NNT * NMT), ij = qij % (NNT * NMT), i = ij / NMT, j = ij % NMT;
+                constexpr int t = ko * 4 * NNT * NMT + qij;  // number of this MFMA within the step
+                acc[ij] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[c * NNT + i][q], bv[c * NMT + j][q],
+                                                               acc[ij], 0, 0, 0);
+                // items [t*NIT/NM, (t+1)*NIT/NM) of the stores-then-loads list ride behind it
+                constexpr int lo = t * NIT / NM, hi = (t + 1) * NIT / NM;
+                static_for<hi - lo>([&](auto D) WPK_LAMBDA {
+                    constexpr int it = lo + decltype(D)::value;
+                    if constexpr (it < NXQ) {
+                        if constexpr (do_store) store_x(cur ^ 1, std::integral_constant<int, it>{});
+                    } else if constexpr (it < NXQ + NW) {
+                        if constexpr (do_store) store_w(cur ^ 1, std::integral_constant<int, it - NXQ>{});
+                    } else if constexpr (it < NXQ + NW + NX) {
+                        if constexpr (do_load) load_x(std::integral_constant<int, it - NXQ - NW>{});
+                    } else {
+                        if constexpr (do_load)
+                            load_w(step + 2, std::integral_constant<int, it - NXQ - NW - NX>{});
+                    }
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+        __syncthreads();
+    };
+    using std::false_type;
+    using std::true_type;
+
     if (kbeg < kend) {
-        gload(kbeg);
-        lstore(0);
-        if (kbeg + 1 < kend) gload(kbeg + 1);
+        load_taps(kbeg);
+        static_for<NX>([&](auto E) WPK_LAMBDA { load_x(E); });
+        static_for<NW>([&](auto E) WPK_LAMBDA { load_w(kbeg, E); });
+        static_for<NXQ>([&](auto E) WPK_LAMBDA { store_x(0, E); });
+        static_for<NW>([&](auto E) WPK_LAMBDA { store_w(0, E); });
+        if (kbeg + 1 < kend) {
+            load_taps(kbeg + 1);
+            static_for<NX>([&](auto E) WPK_LAMBDA { load_x(E); });
+            static_for<NW>([&](auto E) WPK_LAMBDA { load_w(kbeg + 1, E); });
+        }
     }
     __syncthreads();
-    // LDS read instructions per row pair after the compiler pairs neighbouring 32-column blocks
-    constexpr int DSR = (NNT + 1) / 2 + (NMT + 1) / 2;
-    for (int step = kbeg; step < kend; ++step) {
-        const int cur = (step - kbeg) & 1;
-        const float *xs = Xs[cur] + wave_m * TM + lcol + lrow * BM;
-        const float *ws = Ws[cur] + wave_n * TN + lcol + lrow * BN;
-        // operands of row pair kk+2 are fetched from LDS before the MFMAs of row pair kk issue
-        float av[2 * NNT], bv[2 * NMT];
-        static_for<NNT>([&](auto I) WPK_LAMBDA { av[decltype(I)::value] = ws[decltype(I)::value * 32]; });
-        static_for<NMT>([&](auto J) WPK_LAMBDA { bv[decltype(J)::value] = xs[decltype(J)::value * 32]; });
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-        if (step + 1 < kend) lstore(cur ^ 1);
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-        if (step + 2 < kend) gload(step + 2);
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<BK / 2>([&](auto KK) WPK_LAMBDA {
-            constexpr int kk = decltype(KK)::value * 2;
-            constexpr int c = (kk >> 1) & 1, nx = c ^ 1;
-            if constexpr (kk + 2 < BK) {
-                static_for<NNT>([&](auto I) WPK_LAMBDA {
-                    av[nx * NNT + decltype(I)::value] = ws[(kk + 2) * BN + decltype(I)::value * 32];
-                });
-                static_for<NMT>([&](auto J) WPK_LAMBDA {
-                    bv[nx * NMT + decltype(J)::value] = xs[(kk + 2) * BM + decltype(J)::value * 32];
-                });
-                __builtin_amdgcn_sched_group_barrier(0x100, DSR, 0);
-            }
-            static_for<NNT>([&](auto I) WPK_LAMBDA {
-                static_for<NMT>([&](auto J) WPK_LAMBDA {
-                    constexpr int i = decltype(I)::value, j = decltype(J)::value;
-                    acc[i * NMT + j] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                        av[c * NNT + i], bv[c * NMT + j], acc[i * NMT + j], 0, 0, 0);
-                });
-            });
-            __builtin_amdgcn_sched_group_barrier(0x008, NNT * NMT, 0);
-        });
-        __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();
+    int step = kbeg;
+    for (; step + 2 < kend; ++step) step_body(step, true_type{}, true_type{});
+    if (step + 1 < kend) {
+        step_body(step, true_type{}, false_type{});
+        ++step;
     }
+    if (step < kend) step_body(step, false_type{}, false_type{});
 
     // ---- epilogue: D[row = channel][col = pixel]; register e of lane l holds row
     //      8*(e/4) + 4*(l/32) + e%4 and column l%32 of its 32x32 block ---------------------------

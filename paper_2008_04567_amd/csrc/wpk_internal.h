@@ -27,12 +27,17 @@ const int32_t *gene_values(int g);
 // of packed weights and of the tap table never need a bounds check.
 static const int kRedAlign = 32;
 static const int kKoutAlign = 128;
-// Filter taps are tracked in a 64-bit in-bounds mask per pixel; bit 63 is the "never valid"
-// sentinel used by padded reduction rows, so a filter may have at most 63 taps.
-static const int kMaxTaps = 63;
+// Per pixel, filter rows and columns outside the image are tracked in one 32-bit mask: bits
+// 0..15 for rows, bits 16..30 for columns, bit 31 reserved as "always outside" for the padded
+// reduction rows.  So the tiled family takes filters up to 16 rows by 15 columns.
+static const int kMaxFilterRows = 16;
+static const int kMaxFilterCols = 15;
+static const int kPadTapBit = 31;
 static const int kNumXcd = 8;
-static const int kMaxLdsBytes = 64 * 1024;
-// Activation offsets are 32-bit byte offsets with 0x80000000 as the out-of-range marker.
+// LDS per workgroup: two stages of (BM + BN) columns of BK + 4 floats; two workgroups of the
+// largest tile still fit the 160 KB of a compute unit.
+static const int kMaxLdsBytes = 80 * 1024;
+// Tensors are addressed with 32-bit byte offsets through buffer descriptors.
 static const int64_t kMaxTiledBytes = 0x7fffffff;
 
 // ---- one compiled tile combination -------------------------------------------------------------
@@ -61,15 +66,17 @@ std::string desc_key(const wpk_conv_desc *d);
 // Kernel argument block of the tiled implicit-GEMM family (passed by value).
 struct IgemmArgs {
     const float *x;
-    const float *wp;      // packed weights [CRSpad][Kpad], reduction-major
+    const float *wp;      // packed weights [CRSpad/4][Kpad][4]
     float *y;
-    const int32_t *ktab;  // [CRSpad][2]: element offset of the tap in x, tap index r*S+s (63 = pad)
+    const int32_t *ktab;  // [CRSpad][4]: biased byte offset of the tap, mask bit of r, of s, 0
     int32_t N, C, H, W, K, P, Q, R, S;
     int32_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
     int32_t M, PQ, HW, CRS, Kpad;
     int32_t nsteps, steps_per_split, split_k;
     int32_t tiles_m, tiles_n, remap;
-    uint32_t x_bytes;
+    uint32_t x_bytes;   // size of x
+    uint32_t x_bias;    // (pad_h*W + pad_w)*4: added to every tap offset, subtracted from the base
+    uint32_t w_bytes;   // size of the packed weights
 };
 
 // host-side state shared between wpk_host.cpp and wpk_api.hip

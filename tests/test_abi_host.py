@@ -130,7 +130,7 @@ def test_config_encoding_roundtrip_and_constraint_check():
         assert B.config_kernel_name(c).startswith("wpk_igemm_%dx%dx%d_" % (c.bm, c.bn, c.bk))
         # the constraints the header states
         assert 64 * c.wm * c.wn <= 1024
-        assert 2 * c.bk * (c.bm + c.bn) * 4 <= 64 * 1024
+        assert 2 * (c.bk + 4) * (c.bm + c.bn) * 4 <= 80 * 1024
         assert (c.bm // c.wm) % 32 == 0 and (c.bn // c.wn) % 32 == 0
         ids.add(cid)
     assert len(ids) == len(legal)
@@ -139,8 +139,9 @@ def test_config_encoding_roundtrip_and_constraint_check():
     tiny = d13(1, 1, 4, 4, 8, 1, 1)                                            # 1 reduction step
     assert not B.config_legal(tiny, B.make_config(128, 64, 16, 2, 2, split_k=2))
     assert B.config_legal(tiny, B.make_config(128, 64, 16, 2, 2, split_k=1))
-    big_filter = d13(1, 1, 20, 20, 8, 8, 8)                                    # 64 taps > 63
-    assert B.legal_configs(big_filter) == []
+    assert B.legal_configs(d13(1, 1, 20, 20, 8, 17, 2)) == []                  # > 16 filter rows
+    assert B.legal_configs(d13(1, 1, 20, 20, 8, 2, 16)) == []                  # > 15 filter columns
+    assert B.legal_configs(d13(1, 1, 20, 20, 8, 16, 15)) != []
     with pytest.raises(B.WpkError):
         B.config_from_id(10 ** 9)
     with pytest.raises(B.WpkError):

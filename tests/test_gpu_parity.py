@@ -99,9 +99,14 @@ def test_shape_sweep_default_and_fixed_configs(row):
             PT.assert_close(PT.run_gpu(l, x, w, cfg=c_), y_ref, d_ref, name + repr(c_))
 
 
-def test_too_many_taps_uses_the_direct_kernel():
-    l = W.layer("taps64", 1, 2, (12, 12), 3, 8, 1, 2, 1, x_dist="u11", w_dist="u11", seed=5)
-    assert B.legal_configs(B.make_desc(l)) == []
+def test_oversized_filter_uses_the_direct_kernel():
+    # the tiled family tracks at most 16 filter rows and 15 filter columns per pixel
+    for rs in [(17, 2), (2, 16)]:
+        l = W.layer("big_filter", 1, 2, (20, 20), 3, rs, 1, 2, 1, x_dist="u11", w_dist="u11", seed=5)
+        assert B.legal_configs(B.make_desc(l)) == []
+        PT.check_layer(l)
+    l = W.layer("filter_16x15", 1, 2, (20, 19), 3, (16, 15), 1, 3, 1, x_dist="u11", w_dist="u11", seed=6)
+    assert B.legal_configs(B.make_desc(l)) != []
     PT.check_layer(l)
 
 
