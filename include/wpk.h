@@ -77,18 +77,23 @@ int wpk_last_hip_error(void);
 /*
  * Every gene is an integer with a finite range.  A chromosome is legal for a descriptor when
  * wpk_config_legal() says so (the constraint check of Step1): the tile combination must be one
- * the library was built with, its LDS and workgroup size must fit a gfx950 compute unit, and
- * split_k may not exceed the number of reduction steps.
+ * the library was built with, its LDS and workgroup size must fit a gfx950 compute unit,
+ * split_k may not exceed the number of reduction steps, and the persistent schedule excludes
+ * split_k > 1 and xcd_remap.
  */
-#define WPK_N_GENES 7
+#define WPK_N_GENES 9
 typedef struct wpk_conv_config {
-    int32_t bm;        /* output pixels per workgroup tile:      32, 64, 128, 256                    */
+    int32_t bm;        /* output pixels per workgroup tile:      64, 128, 256                        */
     int32_t bn;        /* output channels per workgroup tile:    32, 64, 128                        */
     int32_t bk;        /* reduction (c,r,s) entries per step:    8, 16, 32                          */
     int32_t wm;        /* waves along the pixel dimension:       1, 2, 4                            */
     int32_t wn;        /* waves along the channel dimension:     1, 2, 4                            */
-    int32_t split_k;   /* slices of the reduction done by separate workgroups: 1 .. 16             */
+    int32_t split_k;   /* slices of the reduction done by separate workgroups: 1 .. 16, 20, 24     */
     int32_t xcd_remap; /* 0: tiles in launch order; 1: contiguous tile ranges per XCD              */
+    int32_t persist;   /* 0: one workgroup per tile and slice; 1..4: that many persistent          */
+                       /* workgroups per compute unit, the reduction steps of the tiles that do   */
+                       /* not fill a whole round dealt out evenly among them (split_k must be 1)   */
+    int32_t stages;    /* input tiles in flight in registers between global memory and LDS: 1..3   */
 } wpk_conv_config;
 
 /* Gene ranges as index ranges into the value lists above: lo[g] = 0, hi[g] = count-1.
@@ -215,7 +220,7 @@ int wpk_plan_set_layer_config(wpk_plan *plan, int32_t layer, const wpk_conv_conf
 void wpk_plan_destroy(wpk_plan *plan);
 
 /* ---- introspection used by the benchmark ----------------------------------------------------- */
-/* Name of the device kernel a config launches (static storage), e.g. "wpk_igemm_128x64x16_2x2". */
+/* Name of the device kernel a config launches (static storage), e.g. "wpk_igemm_128x64x16_2x2_p2". */
 const char *wpk_config_kernel_name(const wpk_conv_config *cfg);
 /* Device name and compute-unit count of the current device. */
 int wpk_device_info(char *name, int32_t name_capacity, int32_t *compute_units);

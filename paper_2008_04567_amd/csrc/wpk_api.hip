@@ -27,11 +27,11 @@ namespace wpk {
 
 // ---- dispatch table, same order as kVariants ------------------------------------------------------
 typedef hipError_t (*LaunchFn)(const IgemmArgs &, hipStream_t);
-#define WPK_VARIANT(PART, BM, BN, BK, WM, WN) \
-    extern template hipError_t launch_igemm<BM, BN, BK, WM, WN>(const IgemmArgs &, hipStream_t);
+#define WPK_VARIANT(PART, BM, BN, BK, WM, WN, PD) \
+    extern template hipError_t launch_igemm<BM, BN, BK, WM, WN, PD>(const IgemmArgs &, hipStream_t);
 #include "wpk_variants.def"
 #undef WPK_VARIANT
-#define WPK_VARIANT(PART, BM, BN, BK, WM, WN) &launch_igemm<BM, BN, BK, WM, WN>,
+#define WPK_VARIANT(PART, BM, BN, BK, WM, WN, PD) &launch_igemm<BM, BN, BK, WM, WN, PD>,
 static const LaunchFn kLaunch[] = {
 #include "wpk_variants.def"
 };
@@ -100,6 +100,19 @@ __global__ void fill_zero_kernel(float4 *__restrict__ p4, float *__restrict__ ta
     long long stride = (long long)gridDim.x * blockDim.x;
     for (long long j = i; j < n4; j += stride) p4[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (i < ntail) tail[i] = 0.0f;
+}
+
+// Zero y for all pixels m >= m_begin (every channel): the tiles a persistent launch accumulates
+// into with atomics.  One lane per (channel, pixel), pixels fastest.
+__global__ void zero_pixels_kernel(float *__restrict__ y, int m_begin, int M, int K, int PQ)
+{
+    const long long span = M - m_begin;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < span * K;
+         i += (long long)gridDim.x * blockDim.x) {
+        int m = m_begin + (int)(i % span), k = (int)(i / span);
+        int n = m / PQ, pq = m - n * PQ;
+        y[((long long)n * K + k) * PQ + pq] = 0.0f;
+    }
 }
 
 // Synthetic operands for the tuner: value = lo + (hi-lo) * hash(index, seed) / 2^24.
@@ -227,7 +240,7 @@ static int run_ref(const Problem &pr, const float *x, const float *w, float *y, 
 static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32_t *ktab,
                       const float *x, const float *wp, float *y, hipStream_t st)
 {
-    int vi = find_variant(cfg.bm, cfg.bn, cfg.bk, cfg.wm, cfg.wn);
+    int vi = find_variant(cfg.bm, cfg.bn, cfg.bk, cfg.wm, cfg.wn, cfg.stages);
     if (vi < 0) return WPK_E_NO_CONFIG;
     const wpk_conv_desc &d = pr.d;
     IgemmArgs a;
@@ -237,17 +250,37 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     a.dil_h = d.dil_h; a.dil_w = d.dil_w;
     a.M = (int32_t)pr.M; a.PQ = pr.P * pr.Q; a.HW = d.h * d.w; a.CRS = pr.CRS; a.Kpad = pr.Kpad;
     a.nsteps = (pr.CRS + cfg.bk - 1) / cfg.bk;
-    a.split_k = cfg.split_k;
+    // slices of ceil(nsteps/split_k) steps; launch only as many as are not empty
     a.steps_per_split = (a.nsteps + cfg.split_k - 1) / cfg.split_k;
+    a.split_k = (a.nsteps + a.steps_per_split - 1) / a.steps_per_split;
     a.tiles_m = (int32_t)((pr.M + cfg.bm - 1) / cfg.bm);
     a.tiles_n = (d.k + cfg.bn - 1) / cfg.bn;
     a.remap = cfg.xcd_remap;
     a.x_bytes = (uint32_t)(pr.x_elems * 4);
     a.x_bias = (uint32_t)((d.pad_h * d.w + d.pad_w) * 4);
     a.w_bytes = (uint32_t)((int64_t)pr.CRSpad * pr.Kpad * 4);
-    if (cfg.split_k > 1) {
+    a.persist = cfg.persist;
+    a.grid_persist = cfg.persist * (g_cus > 0 ? g_cus : 256);
+    if (a.split_k > 1) {
         int rc = zero_fill(y, pr.y_elems, st);
         if (rc != WPK_OK) return rc;
+    } else if (cfg.persist > 0) {
+        // tiles beyond the last whole round are accumulated with atomics: zero their pixels
+        int tiles = a.tiles_m * a.tiles_n;
+        int tiles_dp = tiles / a.grid_persist * a.grid_persist;
+        if (tiles_dp < tiles) {
+            int m_begin = tiles_dp / a.tiles_n * cfg.bm;
+            if (m_begin == 0) {
+                int rc = zero_fill(y, pr.y_elems, st);
+                if (rc != WPK_OK) return rc;
+            } else {
+                long long n = (long long)(a.M - m_begin) * a.K;
+                int blocks = (int)std::min<long long>(4096, (n + 255) / 256);
+                hipLaunchKernelGGL(zero_pixels_kernel, dim3(blocks), dim3(256), 0, st, y, m_begin, a.M,
+                                   a.K, a.PQ);
+                WPK_HIP(hipGetLastError());
+            }
+        }
     }
     WPK_HIP(kLaunch[vi](a, st));
     return WPK_OK;
@@ -302,8 +335,10 @@ static int fwd_with(const Problem &pr, const wpk_conv_config &cfg, const float *
                     float *y, hipStream_t st)
 {
     std::lock_guard<std::mutex> g(g_mu);
+    int rc = ensure_device();
+    if (rc != WPK_OK) return rc;
     Prepared *prep;
-    int rc = get_prepared(pr, &prep);
+    rc = get_prepared(pr, &prep);
     if (rc != WPK_OK) return rc;
     float *wp;
     rc = get_wscratch((size_t)pr.CRSpad * pr.Kpad, &wp);
@@ -405,8 +440,8 @@ static double tune_fitness(const int32_t *genes, int32_t n, void *user)
     }
     t->times_us[wpk_config_id(&cfg)] = us;
     if (t->opt.verbose >= 2)
-        fprintf(stderr, "[wpk tune] %-28s split %2d remap %d: %9.2f us\n", wpk_config_kernel_name(&cfg),
-                cfg.split_k, cfg.xcd_remap, us);
+        fprintf(stderr, "[wpk tune] %-32s split %2d remap %d persist %d: %9.2f us\n",
+                wpk_config_kernel_name(&cfg), cfg.split_k, cfg.xcd_remap, cfg.persist, us);
     return 1.0 / us;
 }
 

@@ -20,9 +20,11 @@ const int32_t kBnVals[3] = {32, 64, 128};
 const int32_t kBkVals[3] = {8, 16, 32};
 const int32_t kWmVals[3] = {1, 2, 4};
 const int32_t kWnVals[3] = {1, 2, 4};
-const int32_t kSplitVals[9] = {1, 2, 3, 4, 6, 8, 9, 12, 16};
+const int32_t kSplitVals[18] = {1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 20, 24};
 const int32_t kRemapVals[2] = {0, 1};
-const int kGeneCounts[WPK_N_GENES] = {3, 3, 3, 3, 3, 9, 2};
+const int32_t kPersistVals[5] = {0, 1, 2, 3, 4};
+const int32_t kStageVals[3] = {1, 2, 3};
+const int kGeneCounts[WPK_N_GENES] = {3, 3, 3, 3, 3, 18, 2, 5, 3};
 
 const int32_t *gene_values(int g)
 {
@@ -34,25 +36,29 @@ const int32_t *gene_values(int g)
     case 4: return kWnVals;
     case 5: return kSplitVals;
     case 6: return kRemapVals;
+    case 7: return kPersistVals;
+    case 8: return kStageVals;
     }
     return nullptr;
 }
 
 #define WPK_STR2(x) #x
 #define WPK_STR(x) WPK_STR2(x)
-#define WPK_VARIANT(PART, BM, BN, BK, WM, WN) \
-    {BM, BN, BK, WM, WN, "wpk_igemm_" WPK_STR(BM) "x" WPK_STR(BN) "x" WPK_STR(BK) "_" WPK_STR(WM) "x" WPK_STR(WN)},
+#define WPK_VARIANT(PART, BM, BN, BK, WM, WN, PD)                                                  \
+    {BM, BN, BK, WM, WN, PD,                                                                       \
+     "wpk_igemm_" WPK_STR(BM) "x" WPK_STR(BN) "x" WPK_STR(BK) "_" WPK_STR(WM) "x" WPK_STR(WN) "_p" WPK_STR(PD)},
 const Variant kVariants[] = {
 #include "wpk_variants.def"
 };
 #undef WPK_VARIANT
 const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
-int find_variant(int bm, int bn, int bk, int wm, int wn)
+int find_variant(int bm, int bn, int bk, int wm, int wn, int stages)
 {
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
-        if (v.bm == bm && v.bn == bn && v.bk == bk && v.wm == wm && v.wn == wn) return i;
+        if (v.bm == bm && v.bn == bn && v.bk == bk && v.wm == wm && v.wn == wn && v.stages == stages)
+            return i;
     }
     return -1;
 }
@@ -126,6 +132,8 @@ static const int32_t *cfg_fields(const wpk_conv_config *c, int32_t f[WPK_N_GENES
 {
     f[0] = c->bm; f[1] = c->bn; f[2] = c->bk; f[3] = c->wm; f[4] = c->wn; f[5] = c->split_k;
     f[6] = c->xcd_remap;
+    f[7] = c->persist;
+    f[8] = c->stages;
     return f;
 }
 
@@ -137,13 +145,15 @@ bool legal_for(const Problem &pr, const wpk_conv_config &cfg)
     for (int g = 0; g < WPK_N_GENES; ++g)
         if (value_index(g, f[g]) < 0) return false;
     if (!pr.tiled_ok) return false;
-    if (find_variant(cfg.bm, cfg.bn, cfg.bk, cfg.wm, cfg.wn) < 0) return false;
+    if (find_variant(cfg.bm, cfg.bn, cfg.bk, cfg.wm, cfg.wn, cfg.stages) < 0) return false;
     int threads = 64 * cfg.wm * cfg.wn;
     if (threads > 1024) return false;                                             // workgroup size
     if (2 * (cfg.bk + 4) * (cfg.bm + cfg.bn) * 4 > kMaxLdsBytes) return false;    // two LDS stages
     if (threads > cfg.bm && (cfg.bk * cfg.bm / threads) % 4 != 0) return false;   // whole k quads per thread
     int32_t nsteps = (pr.CRS + cfg.bk - 1) / cfg.bk;
     if (cfg.split_k > nsteps) return false;
+    // the persistent schedule balances the reduction itself: no fixed slices, no tile remap
+    if (cfg.persist > 0 && (cfg.split_k != 1 || cfg.xcd_remap != 0)) return false;
     int64_t tiles = ((pr.M + cfg.bm - 1) / cfg.bm) * ((pr.d.k + cfg.bn - 1) / cfg.bn);
     if (tiles * cfg.split_k > 0x7fffffff) return false;
     return true;
@@ -157,11 +167,11 @@ void default_config(const Problem &pr, int compute_units, wpk_conv_config *out)
 {
     if (compute_units <= 0) compute_units = 256;
     double best = 1e300;
-    wpk_conv_config bc = {128, 64, 16, 2, 2, 1, 1};
+    wpk_conv_config bc = {128, 64, 16, 2, 2, 1, 1, 0, 2};
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
         for (int si = 0; si < kGeneCounts[5]; ++si) {
-            wpk_conv_config c = {v.bm, v.bn, v.bk, v.wm, v.wn, kSplitVals[si], 1};
+            wpk_conv_config c = {v.bm, v.bn, v.bk, v.wm, v.wn, kSplitVals[si], 1, 0, v.stages};
             if (!legal_for(pr, c)) continue;
             double nsteps = ceil((double)pr.CRS / v.bk);
             double steps = ceil(nsteps / c.split_k);
@@ -339,6 +349,8 @@ int wpk_config_from_genes(const int32_t genes[WPK_N_GENES], wpk_conv_config *out
     out->wn = kWnVals[genes[4]];
     out->split_k = kSplitVals[genes[5]];
     out->xcd_remap = kRemapVals[genes[6]];
+    out->persist = kPersistVals[genes[7]];
+    out->stages = kStageVals[genes[8]];
     return WPK_OK;
 }
 
@@ -390,7 +402,7 @@ int wpk_config_from_id(int id, wpk_conv_config *out)
 const char *wpk_config_kernel_name(const wpk_conv_config *cfg)
 {
     if (!cfg) return "";
-    int i = find_variant(cfg->bm, cfg->bn, cfg->bk, cfg->wm, cfg->wn);
+    int i = find_variant(cfg->bm, cfg->bn, cfg->bk, cfg->wm, cfg->wn, cfg->stages);
     return i < 0 ? "" : kVariants[i].name;
 }
 
@@ -440,13 +452,13 @@ int wpk_cache_save(const char *path)
     FILE *f = fopen(path, "w");
     if (!f) return WPK_E_IO;
     std::lock_guard<std::mutex> g(g_cache_mu);
-    fprintf(f, "# wpk search-result cache v1: key bm bn bk wm wn split_k xcd_remap microseconds\n");
+    fprintf(f, "# wpk search-result cache v2: key bm bn bk wm wn split_k xcd_remap persist stages microseconds\n");
     for (auto &kv : g_cache) {
         std::string key = kv.first;
         std::replace(key.begin(), key.end(), ' ', '_');
         const wpk_conv_config &c = kv.second.cfg;
-        fprintf(f, "%s %d %d %d %d %d %d %d %.6f\n", key.c_str(), c.bm, c.bn, c.bk, c.wm, c.wn,
-                c.split_k, c.xcd_remap, kv.second.us);
+        fprintf(f, "%s %d %d %d %d %d %d %d %d %d %.6f\n", key.c_str(), c.bm, c.bn, c.bk, c.wm, c.wn,
+                c.split_k, c.xcd_remap, c.persist, c.stages, kv.second.us);
     }
     return fclose(f) == 0 ? WPK_OK : WPK_E_IO;
 }
@@ -464,8 +476,8 @@ int wpk_cache_load(const char *path)
         char key[512];
         wpk_conv_config c;
         double us;
-        if (sscanf(line, "%511s %d %d %d %d %d %d %d %lf", key, &c.bm, &c.bn, &c.bk, &c.wm, &c.wn,
-                   &c.split_k, &c.xcd_remap, &us) != 9)
+        if (sscanf(line, "%511s %d %d %d %d %d %d %d %d %d %lf", key, &c.bm, &c.bn, &c.bk, &c.wm, &c.wn,
+                   &c.split_k, &c.xcd_remap, &c.persist, &c.stages, &us) != 11)
             continue;
         int32_t genes[WPK_N_GENES];
         if (wpk_config_to_genes(&c, genes) != WPK_OK) continue;

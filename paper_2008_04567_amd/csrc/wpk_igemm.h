@@ -72,7 +72,7 @@ typedef const int __attribute__((address_space(4))) *tap_ptr;
 // LDS row pitch (floats) of a reduction-contiguous tile with BK k values per column.
 __host__ __device__ constexpr int lds_pitch(int bk) { return bk + 4; }
 
-template <int BM, int BN, int BK, int WM, int WN>
+template <int BM, int BN, int BK, int WM, int WN, int PD>
 __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
 {
     constexpr int T = 64 * WM * WN;
@@ -91,6 +91,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     static_assert(BK % RG == 0 && XR % 4 == 0, "a thread must own whole k quads");
     static_assert((T >= BM && T % BM == 0) || (T < BM && BM % T == 0), "gather mapping");
     static_assert(T % BN == 0, "weight quads: every thread keeps one channel");
+    static_assert(PD >= 1 && PD <= 4, "one to four tiles in flight");
 
     __shared__ __attribute__((aligned(16))) float lds[2 * (XTILE + WTILE)];
     float *const Xs0 = lds, *const Ws0 = lds + 2 * XTILE;
@@ -101,12 +102,22 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     const int wave_m = wave % WM, wave_n = wave / WM;
     const int lrow = lane >> 5, lcol = lane & 31;
 
-    int bid = blockIdx.x;
-    if (a.remap) bid = xcd_remap(bid, gridDim.x);
-    const int tile_n = bid % a.tiles_n;
-    const int t2 = bid / a.tiles_n;
-    const int tile_m = t2 % a.tiles_m;
-    const int split = t2 / a.tiles_m;
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)((const char *)a.x - a.x_bias), 0, (int)(a.x_bytes + a.x_bias), 0x00020000);
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.wp, 0, (int)a.w_bytes, 0x00020000);
+    const tap_ptr taps = (tap_ptr)(unsigned long long)a.ktab;
+    const int pm0 = tid % (T < BM ? T : BM);
+    const int rg = __builtin_amdgcn_readfirstlane(tid / BM);  // 0 when T <= BM
+    const int wkout = tid % BN, wkq = tid / BN;      // weight quads: this thread's channel, k quad
+    const int wstep_bytes = (BK / 4) * a.Kpad * 16;  // one reduction step further
+    const int wquad_bytes = (T / BN) * a.Kpad * 16;  // this thread's next quad in the same step
+
+    // One segment of work: reduction steps [kbeg, kend) of output tile `tile`, written with plain
+    // stores, or added with atomics when other workgroups hold the rest of the reduction.
+    auto run_segment = [&](const int tile, const int kbeg, const int kend, const bool atomic) WPK_LAMBDA {
+    if (kbeg >= kend) return;  // nothing to reduce: touch neither the tap table nor y
+    const int tile_n = tile % a.tiles_n, tile_m = tile / a.tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     // ---- per-thread gather state ---------------------------------------------------------------
@@ -114,8 +125,6 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     //        shift is folded into the tap offsets and the buffer base, so it is never negative);
     // xinv : bit r set = filter row r is outside the image for this pixel, bit 16+s = column s;
     //        bit 31 is always set and is what the table's padding rows point at.
-    const int pm0 = tid % (T < BM ? T : BM);
-    const int rg = __builtin_amdgcn_readfirstlane(tid / BM);  // 0 when T <= BM
     int xvoff[XP];
     unsigned xinv[XP];
     static_for<XP>([&](auto I) WPK_LAMBDA {
@@ -140,24 +149,15 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
             xinv[i] = inv;
         }
     });
-    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)((const char *)a.x - a.x_bias), 0, (int)(a.x_bytes + a.x_bias), 0x00020000);
-    const __amdgpu_buffer_rsrc_t wrsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void *)a.wp, 0, (int)a.w_bytes, 0x00020000);
-    const tap_ptr taps = (tap_ptr)(unsigned long long)a.ktab;
-    // weight quads: this thread's channel and first k quad inside the tile
-    const int wkout = tid % BN, wkq = tid / BN;
     const int wvoff = (wkq * a.Kpad + n0 + wkout) * 16;
-    const int wstep_bytes = (BK / 4) * a.Kpad * 16;  // one reduction step further
-    const int wquad_bytes = (T / BN) * a.Kpad * 16;  // this thread's next quad in the same step
 
-    // ---- staging registers: one tile (activations and weights) in flight between global memory
-    //      and LDS ---------------------------------------------------------------------------------
-    constexpr int NX = XP * XR;   // activation dwords per thread
+    // ---- staging registers: PD tiles (activations and weights) in flight between global memory
+    //      and LDS.  Tile number r of the segment (r = step - kbeg) travels in set r % PD. ---------
+    constexpr int NX = XP * XR;   // activation dwords per thread and tile
     constexpr int NXQ = NX / 4;   // ... stored to LDS as quads
-    constexpr int NW = WL;        // weight quads per thread
-    float xr[NX];
-    v4f wr[NW];
+    constexpr int NW = WL;        // weight quads per thread and tile
+    float xr[PD * NX];
+    v4f wr[PD * NW];
     int tap_off[XR], tap_r[XR], tap_s[XR];  // wave-uniform: live in scalar registers
 
     // A row group owns XR consecutive reduction rows of the step, so its tap-table entries are
@@ -171,32 +171,43 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
             tap_s[jj] = tp[4 * jj + 2];
         });
     };
-    // global -> register: activation dword E of the tile
-    auto load_x = [&](auto E) WPK_LAMBDA {
-        constexpr int e = decltype(E)::value, i = e / XR, jj = e % XR;
+    // global -> register set SET: activation dword E of the tile whose taps are loaded
+    auto load_x = [&](auto SET, auto E) WPK_LAMBDA {
+        constexpr int set = decltype(SET)::value, e = decltype(E)::value, i = e / XR, jj = e % XR;
         int bad = __builtin_amdgcn_sbfe((int)xinv[i], tap_r[jj], 1) |
                   __builtin_amdgcn_sbfe((int)xinv[i], tap_s[jj], 1);  // 0 or all ones
-        xr[e] = __builtin_bit_cast(
+        xr[set * NX + e] = __builtin_bit_cast(
             float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, xvoff[i] | bad, tap_off[jj], 0));
     };
-    // global -> register: weight quad E of the tile of `step`
-    auto load_w = [&](int step, auto E) WPK_LAMBDA {
-        constexpr int i = decltype(E)::value;
+    // global -> register set SET: weight quad E of the tile of `step`
+    auto load_w = [&](auto SET, int step, auto E) WPK_LAMBDA {
+        constexpr int set = decltype(SET)::value, i = decltype(E)::value;
         if (W4 % T == 0 || wkq + i * (T / BN) < BK / 4)
-            wr[i] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(
-                                                wrsrc, wvoff, step * wstep_bytes + i * wquad_bytes, 0));
+            wr[set * NW + i] = __builtin_bit_cast(
+                v4f, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wvoff,
+                                                           step * wstep_bytes + i * wquad_bytes, 0));
     };
-    // register -> LDS buffer `buf`
-    auto store_x = [&](int buf, auto E) WPK_LAMBDA {
-        constexpr int e = decltype(E)::value, i = e / (XR / 4), j4 = e % (XR / 4);
-        v4f v = {xr[i * XR + 4 * j4], xr[i * XR + 4 * j4 + 1], xr[i * XR + 4 * j4 + 2],
-                 xr[i * XR + 4 * j4 + 3]};
+    // register set SET -> LDS buffer `buf`
+    auto store_x = [&](auto SET, int buf, auto E) WPK_LAMBDA {
+        constexpr int set = decltype(SET)::value, e = decltype(E)::value;
+        constexpr int i = e / (XR / 4), j4 = e % (XR / 4), b = set * NX + i * XR + 4 * j4;
+        v4f v = {xr[b], xr[b + 1], xr[b + 2], xr[b + 3]};
         *reinterpret_cast<v4f *>(Xs0 + buf * XTILE + (pm0 + i * T) * PX + rg * XR + 4 * j4) = v;
     };
-    auto store_w = [&](int buf, auto E) WPK_LAMBDA {
-        constexpr int i = decltype(E)::value;
+    auto store_w = [&](auto SET, int buf, auto E) WPK_LAMBDA {
+        constexpr int set = decltype(SET)::value, i = decltype(E)::value;
         if (W4 % T == 0 || wkq + i * (T / BN) < BK / 4)
-            *reinterpret_cast<v4f *>(Ws0 + buf * WTILE + wkout * PW + (wkq + i * (T / BN)) * 4) = wr[i];
+            *reinterpret_cast<v4f *>(Ws0 + buf * WTILE + wkout * PW + (wkq + i * (T / BN)) * 4) =
+                wr[set * NW + i];
+    };
+    auto load_tile = [&](auto SET, int step) WPK_LAMBDA {
+        load_taps(step);
+        static_for<NX>([&](auto E) WPK_LAMBDA { load_x(SET, E); });
+        static_for<NW>([&](auto E) WPK_LAMBDA { load_w(SET, step, E); });
+    };
+    auto store_tile = [&](auto SET, int buf) WPK_LAMBDA {
+        static_for<NXQ>([&](auto E) WPK_LAMBDA { store_x(SET, buf, E); });
+        static_for<NW>([&](auto E) WPK_LAMBDA { store_w(SET, buf, E); });
     };
 
     v16f acc[NNT * NMT];
@@ -204,21 +215,19 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
         static_for<16>([&](auto E) WPK_LAMBDA { acc[decltype(I)::value][decltype(E)::value] = 0.0f; });
     });
 
-    const int kbeg = split * a.steps_per_split;
-    const int kend = min(a.nsteps, kbeg + a.steps_per_split);
-
-    // One reduction step.  Three-deep pipeline over two LDS buffers: the MFMAs of step s read
-    // buffer s&1; meanwhile the tile of step s+1 (in the staging registers since the previous
-    // step) is stored to the other buffer (STORE) and then the tile of step s+2 is loaded from
-    // global memory into the same registers (LOAD).  These stores and loads are dealt out one by
-    // one behind the individual MFMAs, each of which keeps the matrix pipe busy for 64 cycles, so
-    // they issue in its shadow; the LDS operands of octet o+1 are read before the MFMAs of octet
-    // o.  One barrier per step, at its end.
+    // One reduction step, r-th of the segment.  The MFMAs read LDS buffer r&1.  Meanwhile tile
+    // r+1, which has been in staging set (r+1)%PD since step r-PD, is stored to the other buffer
+    // and tile r+1+PD is loaded from global memory into the set it frees, so a load has PD steps
+    // to arrive.  In the main loop (INTERLEAVE) these stores and loads are dealt out one by one
+    // behind the individual MFMAs, each of which keeps the matrix pipe busy for 64 cycles, so they
+    // issue in its shadow; the LDS operands of octet o+1 are read before the MFMAs of octet o.
+    // The last steps of a segment (no more tiles to load or store) run the plain form, with
+    // whatever store and load is left done up front.  One barrier per step, at its end.
     constexpr int NM = (BK / 2) * NNT * NMT;       // MFMAs per step and wave
     constexpr int NIT = NXQ + NW + NX + NW;        // stores (x, w) then loads (x, w)
-    auto step_body = [&](int step, auto STORE, auto LOAD) WPK_LAMBDA {
-        constexpr bool do_store = decltype(STORE)::value, do_load = decltype(LOAD)::value;
-        const int cur = (step - kbeg) & 1;
+    auto step_body = [&](const int r, auto SET, auto INTERLEAVE) WPK_LAMBDA {
+        constexpr bool inter = decltype(INTERLEAVE)::value;
+        const int cur = r & 1;
         const float *xs = Xs0 + cur * XTILE + (wave_m * TM + lcol) * PX + lrow * 4;
         const float *ws = Ws0 + cur * WTILE + (wave_n * TN + lcol) * PW + lrow * 4;
         v4f av[2 * NNT], bv[2 * NMT];
@@ -228,7 +237,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
         static_for<NMT>([&](auto J) WPK_LAMBDA {
             bv[decltype(J)::value] = *reinterpret_cast<const v4f *>(xs + decltype(J)::value * 32 * PX);
         });
-        if constexpr (do_load) load_taps(step + 2);
+        if constexpr (inter) load_taps(kbeg + r + 1 + PD);
         __builtin_amdgcn_sched_barrier(0);
         static_for<BK / 8>([&](auto KO) WPK_LAMBDA {
             constexpr int ko = decltype(KO)::value;
@@ -250,21 +259,21 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                 constexpr int t = ko * 4 * NNT * NMT + qij;  // number of this MFMA within the step
                 acc[ij] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[c * NNT + i][q], bv[c * NMT + j][q],
                                                                acc[ij], 0, 0, 0);
-                // items [t*NIT/NM, (t+1)*NIT/NM) of the stores-then-loads list ride behind it
-                constexpr int lo = t * NIT / NM, hi = (t + 1) * NIT / NM;
-                static_for<hi - lo>([&](auto D) WPK_LAMBDA {
-                    constexpr int it = lo + decltype(D)::value;
-                    if constexpr (it < NXQ) {
-                        if constexpr (do_store) store_x(cur ^ 1, std::integral_constant<int, it>{});
-                    } else if constexpr (it < NXQ + NW) {
-                        if constexpr (do_store) store_w(cur ^ 1, std::integral_constant<int, it - NXQ>{});
-                    } else if constexpr (it < NXQ + NW + NX) {
-                        if constexpr (do_load) load_x(std::integral_constant<int, it - NXQ - NW>{});
-                    } else {
-                        if constexpr (do_load)
-                            load_w(step + 2, std::integral_constant<int, it - NXQ - NW - NX>{});
-                    }
-                });
+                if constexpr (inter) {
+                    // items [t*NIT/NM, (t+1)*NIT/NM) of the stores-then-loads list ride behind it
+                    constexpr int lo = t * NIT / NM, hi = (t + 1) * NIT / NM;
+                    static_for<hi - lo>([&](auto D) WPK_LAMBDA {
+                        constexpr int it = lo + decltype(D)::value;
+                        if constexpr (it < NXQ)
+                            store_x(SET, cur ^ 1, std::integral_constant<int, it>{});
+                        else if constexpr (it < NXQ + NW)
+                            store_w(SET, cur ^ 1, std::integral_constant<int, it - NXQ>{});
+                        else if constexpr (it < NXQ + NW + NX)
+                            load_x(SET, std::integral_constant<int, it - NXQ - NW>{});
+                        else
+                            load_w(SET, kbeg + r + 1 + PD, std::integral_constant<int, it - NXQ - NW - NX>{});
+                    });
+                }
                 __builtin_amdgcn_sched_barrier(0);
             });
         });
@@ -273,30 +282,36 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     using std::false_type;
     using std::true_type;
 
-    if (kbeg < kend) {
-        load_taps(kbeg);
-        static_for<NX>([&](auto E) WPK_LAMBDA { load_x(E); });
-        static_for<NW>([&](auto E) WPK_LAMBDA { load_w(kbeg, E); });
-        static_for<NXQ>([&](auto E) WPK_LAMBDA { store_x(0, E); });
-        static_for<NW>([&](auto E) WPK_LAMBDA { store_w(0, E); });
-        if (kbeg + 1 < kend) {
-            load_taps(kbeg + 1);
-            static_for<NX>([&](auto E) WPK_LAMBDA { load_x(E); });
-            static_for<NW>([&](auto E) WPK_LAMBDA { load_w(kbeg + 1, E); });
-        }
-    }
+    // prologue: tile 0 straight into LDS buffer 0, tiles 1..PD into their staging sets
+    const int nr = kend - kbeg;
+    load_tile(std::integral_constant<int, 0>{}, kbeg);
+    store_tile(std::integral_constant<int, 0>{}, 0);
+    static_for<PD>([&](auto P) WPK_LAMBDA {
+        constexpr int t = decltype(P)::value + 1;
+        if (t < nr) load_tile(std::integral_constant<int, t % PD>{}, kbeg + t);
+    });
     __syncthreads();
-    int step = kbeg;
-    for (; step + 2 < kend; ++step) step_body(step, true_type{}, true_type{});
-    if (step + 1 < kend) {
-        step_body(step, true_type{}, false_type{});
-        ++step;
+    int r = 0;
+    // main loop: every step still has a tile to store (r+1) and one to load (r+1+PD)
+    for (; r + 2 * PD < nr; r += PD)
+        static_for<PD>([&](auto P) WPK_LAMBDA {
+            constexpr int p = decltype(P)::value;
+            step_body(r + p, std::integral_constant<int, (p + 1) % PD>{}, true_type{});
+        });
+    // tail: at most 2*PD steps
+    for (; r < nr; ++r) {
+        const int set = (r + 1) % PD;
+        static_for<PD>([&](auto P) WPK_LAMBDA {
+            if (set == decltype(P)::value) {
+                if (r + 1 < nr) store_tile(P, (r & 1) ^ 1);
+                if (r + 1 + PD < nr) load_tile(P, kbeg + r + 1 + PD);
+            }
+        });
+        step_body(r, std::integral_constant<int, 0>{}, false_type{});
     }
-    if (step < kend) step_body(step, false_type{}, false_type{});
 
     // ---- epilogue: D[row = channel][col = pixel]; register e of lane l holds row
     //      8*(e/4) + 4*(l/32) + e%4 and column l%32 of its 32x32 block ---------------------------
-    const bool atomic = a.split_k > 1;
     static_for<NMT>([&](auto J) WPK_LAMBDA {
         constexpr int j = decltype(J)::value;
         int m = m0 + wave_m * TM + j * 32 + lcol;
@@ -319,13 +334,58 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
             });
         }
     });
+    };  // run_segment
+
+    // ---- which segments this workgroup runs ----------------------------------------------------
+    // persist == 0: one workgroup per (tile, reduction slice): blockIdx -> tile, slice.
+    // persist  > 0: gridDim.x persistent workgroups.  Each first takes whole tiles g, g+G, ... of
+    //   the first tiles_dp = floor(tiles/G)*G tiles; the steps of the remaining tiles, laid end to
+    //   end, are then cut into G equal runs, one per workgroup, so every workgroup does the same
+    //   number of steps (+-1).  A run that does not cover a tile's whole reduction adds its part
+    //   with atomics into y, which the host has zeroed for those tiles.
+    const int tiles = a.tiles_m * a.tiles_n;
+    const bool persistent = a.persist > 0;
+    const int G = gridDim.x, g = blockIdx.x;
+    const int tiles_dp = persistent ? tiles / G * G : 0;
+    const long long units = (long long)(tiles - tiles_dp) * a.nsteps;
+    int next_dp = g;
+    long long u0 = persistent ? units * g / G : 0;
+    const long long u1 = persistent ? units * (g + 1) / G : 0;
+    bool once = !persistent;
+    for (;;) {
+        int tile, kbeg, kend;
+        bool atomic;
+        if (once) {
+            once = false;
+            int bid = a.remap ? xcd_remap(g, G) : g;
+            tile = bid % tiles;
+            kbeg = (bid / tiles) * a.steps_per_split;
+            kend = min(a.nsteps, kbeg + a.steps_per_split);
+            atomic = a.split_k > 1;
+        } else if (persistent && next_dp < tiles_dp) {
+            tile = next_dp;
+            kbeg = 0;
+            kend = a.nsteps;
+            next_dp += G;
+            atomic = false;
+        } else if (persistent && u0 < u1) {
+            tile = tiles_dp + (int)(u0 / a.nsteps);
+            kbeg = (int)(u0 % a.nsteps);
+            kend = (int)min((long long)a.nsteps, kbeg + (u1 - u0));
+            u0 += kend - kbeg;
+            atomic = !(kbeg == 0 && kend == a.nsteps);
+        } else {
+            break;
+        }
+        run_segment(tile, kbeg, kend, atomic);
+    }
 }
 
-template <int BM, int BN, int BK, int WM, int WN>
+template <int BM, int BN, int BK, int WM, int WN, int PD>
 hipError_t launch_igemm(const IgemmArgs &a, hipStream_t stream)
 {
-    dim3 grid((unsigned)(a.tiles_m * a.tiles_n * a.split_k));
-    hipLaunchKernelGGL((igemm_kernel<BM, BN, BK, WM, WN>), grid, dim3(64 * WM * WN), 0, stream, a);
+    dim3 grid((unsigned)(a.persist > 0 ? a.grid_persist : a.tiles_m * a.tiles_n * a.split_k));
+    hipLaunchKernelGGL((igemm_kernel<BM, BN, BK, WM, WN, PD>), grid, dim3(64 * WM * WN), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -7,9 +7,9 @@
 #endif
 
 namespace wpk {
-#define WPK_EMIT(BM, BN, BK, WM, WN) \
-    template hipError_t launch_igemm<BM, BN, BK, WM, WN>(const IgemmArgs &, hipStream_t);
-#define WPK_SKIP(BM, BN, BK, WM, WN)
+#define WPK_EMIT(BM, BN, BK, WM, WN, PD) \
+    template hipError_t launch_igemm<BM, BN, BK, WM, WN, PD>(const IgemmArgs &, hipStream_t);
+#define WPK_SKIP(BM, BN, BK, WM, WN, PD)
 #define WPK_SEL_0 WPK_SKIP
 #define WPK_SEL_1 WPK_SKIP
 #define WPK_SEL_2 WPK_SKIP
@@ -43,7 +43,7 @@ namespace wpk {
 #undef WPK_SEL_7
 #define WPK_SEL_7 WPK_EMIT
 #endif
-#define WPK_VARIANT(PART, BM, BN, BK, WM, WN) WPK_SEL_##PART(BM, BN, BK, WM, WN)
+#define WPK_VARIANT(PART, BM, BN, BK, WM, WN, PD) WPK_SEL_##PART(BM, BN, BK, WM, WN, PD)
 #include "wpk_variants.def"
 #undef WPK_VARIANT
 }  // namespace wpk

@@ -17,8 +17,10 @@ extern const int32_t kBnVals[3];     // 32, 64, 128
 extern const int32_t kBkVals[3];     // 8, 16, 32
 extern const int32_t kWmVals[3];     // 1, 2, 4
 extern const int32_t kWnVals[3];     // 1, 2, 4
-extern const int32_t kSplitVals[9];  // 1, 2, 3, 4, 6, 8, 9, 12, 16
+extern const int32_t kSplitVals[18]; // 1 .. 16, 20, 24
 extern const int32_t kRemapVals[2];  // 0, 1
+extern const int32_t kStageVals[3];   // 1, 2, 3 tiles in flight in registers
+extern const int32_t kPersistVals[5]; // 0 (off), 1, 2, 3, 4 workgroups per compute unit
 extern const int kGeneCounts[WPK_N_GENES];
 const int32_t *gene_values(int g);
 
@@ -42,12 +44,12 @@ static const int64_t kMaxTiledBytes = 0x7fffffff;
 
 // ---- one compiled tile combination -------------------------------------------------------------
 struct Variant {
-    int32_t bm, bn, bk, wm, wn;
+    int32_t bm, bn, bk, wm, wn, stages;
     const char *name;
 };
 extern const Variant kVariants[];
 extern const int kNumVariants;
-int find_variant(int bm, int bn, int bk, int wm, int wn);  // index or -1
+int find_variant(int bm, int bn, int bk, int wm, int wn, int stages);  // index or -1
 
 // ---- everything derived from one descriptor ------------------------------------------------------
 struct Problem {
@@ -74,6 +76,8 @@ struct IgemmArgs {
     int32_t M, PQ, HW, CRS, Kpad;
     int32_t nsteps, steps_per_split, split_k;
     int32_t tiles_m, tiles_n, remap;
+    int32_t persist;       // 0, or persistent workgroups per compute unit
+    int32_t grid_persist;  // persist * compute units
     uint32_t x_bytes;   // size of x
     uint32_t x_bias;    // (pad_h*W + pad_w)*4: added to every tap offset, subtracted from the base
     uint32_t w_bytes;   // size of the packed weights

@@ -55,7 +55,7 @@ int main(void) {
                    ctypes.sizeof(B.TuneOptions), ctypes.sizeof(B.TuneReport),
                    B.TuneOptions.seed.offset, B.TuneOptions.min_group_us.offset,
                    B.TuneReport.best_us.offset, B.TuneReport.seconds.offset]
-    assert got[0] == 60 and got[1] == 28
+    assert got[0] == 60 and got[1] == 36
 
 
 def d13(n, c, h, w, k, r, s, st=(1, 1), pd=(0, 0), dl=(1, 1)):
@@ -118,16 +118,16 @@ def test_error_codes():
 
 def test_config_encoding_roundtrip_and_constraint_check():
     lo, hi = B.config_gene_ranges()
-    assert lo == [0] * 7 and hi == [2, 2, 2, 2, 2, 8, 1]
+    assert lo == [0] * 9 and hi == [2, 2, 2, 2, 2, 17, 1, 4, 2]
     d = B.make_desc(W.config3()[1])
     legal = B.legal_configs(d)
-    assert 300 < len(legal) < 2000
+    assert 3000 < len(legal) < 15000
     ids = set()
     for c in legal:
         cid = B.config_id(c)
         assert B.config_from_id(cid).astuple() == c.astuple()
         assert B.config_from_genes(B.config_to_genes(c)).astuple() == c.astuple()
-        assert B.config_kernel_name(c).startswith("wpk_igemm_%dx%dx%d_" % (c.bm, c.bn, c.bk))
+        assert B.config_kernel_name(c) == "wpk_igemm_%dx%dx%d_%dx%d_p%d" % (c.bm, c.bn, c.bk, c.wm, c.wn, c.stages)
         # the constraints the header states
         assert 64 * c.wm * c.wn <= 1024
         assert 2 * (c.bk + 4) * (c.bm + c.bn) * 4 <= 80 * 1024
@@ -139,6 +139,10 @@ def test_config_encoding_roundtrip_and_constraint_check():
     tiny = d13(1, 1, 4, 4, 8, 1, 1)                                            # 1 reduction step
     assert not B.config_legal(tiny, B.make_config(128, 64, 16, 2, 2, split_k=2))
     assert B.config_legal(tiny, B.make_config(128, 64, 16, 2, 2, split_k=1))
+    assert B.config_legal(d, B.make_config(128, 64, 16, 2, 2, persist=2))
+    assert not B.config_legal(d, B.ConvConfig(128, 64, 16, 2, 2, 2, 0, 2, 2))   # persistent + split
+    assert not B.config_legal(d, B.ConvConfig(128, 64, 16, 2, 2, 1, 1, 2, 2))   # persistent + remap
+    assert not B.config_legal(d, B.ConvConfig(128, 64, 16, 2, 2, 1, 1, 0, 4))   # stages not in list
     assert B.legal_configs(d13(1, 1, 20, 20, 8, 17, 2)) == []                  # > 16 filter rows
     assert B.legal_configs(d13(1, 1, 20, 20, 8, 2, 16)) == []                  # > 15 filter columns
     assert B.legal_configs(d13(1, 1, 20, 20, 8, 16, 15)) != []
@@ -161,7 +165,7 @@ def test_cache_roundtrip_and_identity_criterion(tmp_path):
     a, b = W.config3()[0], W.config3()[1]
     da, db = B.make_desc(a), B.make_desc(b)
     assert B.cache_lookup(da) is None
-    ca = B.make_config(128, 64, 16, 2, 2, 1, 0)
+    ca = B.make_config(128, 64, 16, 2, 2, 1, 0, 2)
     B.cache_store(da, ca, 12.5)
     assert B.cache_lookup(da).astuple() == ca.astuple()
     assert B.cache_lookup(db) is None

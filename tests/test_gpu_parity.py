@@ -38,12 +38,30 @@ def test_every_tile_variant_on_a_ragged_shape():
     desc = B.make_desc(RAGGED)
     x, w = W.make_inputs(RAGGED)
     y_ref, d_ref = PT.oracle_full(RAGGED, x, w)
-    cfgs = B.legal_configs(desc, split_k=[1], xcd_remap=1)
-    assert len(cfgs) >= 40
+    cfgs = B.legal_configs(desc, split_k=[1], xcd_remap=1, persist=[0])
+    assert len(cfgs) >= 120          # every tile combination at every prefetch depth
     for c in cfgs:
         print(c, flush=True)
         y = PT.run_gpu(RAGGED, x, w, cfg=c)
         PT.assert_close(y, y_ref, d_ref, repr(c))
+
+
+def test_persistent_schedule():
+    """Persistent workgroups: whole rounds of tiles stored plainly, the rest accumulated with
+    atomics into zeroed outputs -- on a shape with more tiles than workgroups (several rounds plus
+    a remainder) and on one with fewer (everything split)."""
+    many = W.layer("many_tiles", 6, 12, (60, 64), 40, 3, 1, 1, x_dist="u11", w_dist="u11", seed=78)
+    for l in (RAGGED, many):
+        desc = B.make_desc(l)
+        x, w = W.make_inputs(l)
+        y_ref, d_ref = PT.oracle_full(l, x, w)
+        for (bm, bn, bk, wm, wn) in [(64, 32, 16, 2, 1), (128, 64, 32, 4, 2), (64, 64, 8, 2, 1)]:
+            for persist in (1, 2, 3, 4):
+                c = B.make_config(bm, bn, bk, wm, wn, persist=persist, stages=1 + persist % 3)
+                assert B.config_legal(desc, c)
+                print(l["name"], c, flush=True)
+                y = PT.run_gpu(l, x, w, cfg=c)
+                PT.assert_close(y, y_ref, d_ref, repr(c))
 
 
 def test_split_k_and_remap_settings():
@@ -51,9 +69,9 @@ def test_split_k_and_remap_settings():
     x, w = W.make_inputs(RAGGED)
     y_ref, d_ref = PT.oracle_full(RAGGED, x, w)
     for (bm, bn, bk, wm, wn) in [(128, 64, 16, 2, 2), (64, 64, 8, 2, 2), (256, 128, 32, 4, 2)]:
-        for split in (2, 3, 4, 6, 8, 9, 12, 16):
+        for split in (2, 3, 5, 7, 8, 11, 16, 20, 24):
             for remap in (0, 1):
-                c = B.make_config(bm, bn, bk, wm, wn, split, remap)
+                c = B.make_config(bm, bn, bk, wm, wn, split, remap, stages=1 + split % 3)
                 if not B.config_legal(desc, c):
                     continue
                 print(c, flush=True)
@@ -93,7 +111,8 @@ def test_shape_sweep_default_and_fixed_configs(row):
     print(name, "default", B.config_default(desc), flush=True)
     PT.assert_close(PT.run_gpu(l, x, w), y_ref, d_ref, name + " default")
     for c_ in [B.make_config(64, 32, 8, 2, 1), B.make_config(128, 128, 16, 2, 2),
-               B.make_config(256, 64, 32, 4, 1), B.make_config(128, 64, 16, 4, 2, 2, 0)]:
+               B.make_config(256, 64, 32, 4, 1, stages=3), B.make_config(128, 64, 16, 4, 2, 2, 0, stages=1),
+               B.make_config(64, 64, 32, 2, 2, persist=2, stages=3)]:
         if B.config_legal(desc, c_):
             print(name, c_, flush=True)
             PT.assert_close(PT.run_gpu(l, x, w, cfg=c_), y_ref, d_ref, name + repr(c_))
