@@ -130,12 +130,12 @@ int wpk_conv2d_ref(const wpk_conv_desc *d, const float *x, const float *w, float
 
 /* ---- tuning (Section 2.3 "Genetic search", Steps 1-4; cache: Section 3.3) --------------------- */
 typedef struct wpk_tune_options {
-    int32_t population;   /* |a|, default 24                                                     */
-    int32_t elites;       /* k, default 4                                                        */
+    int32_t population;   /* |a|, default 48                                                     */
+    int32_t elites;       /* k, default 6                                                        */
     int32_t next_population; /* |a'|, default = population                                        */
     int32_t participants; /* m, default = population                                              */
-    int32_t max_generations; /* default 12                                                       */
-    int32_t patience;     /* stop after this many generations without a better best, default 4   */
+    int32_t max_generations; /* default 16                                                       */
+    int32_t patience;     /* stop after this many generations without a better best, default 5   */
     double  mutation;     /* per-gene mutation probability, default 0.15                         */
     double  eps;          /* Step4: all runtimes within eps of the fastest, default 0.03         */
     uint64_t seed;        /* default 2008                                                        */

@@ -160,25 +160,40 @@ static int ensure_device()
     return WPK_OK;
 }
 
-// Tap table of a problem, four ints per reduction row kk = (c*R + r)*S + s: the byte offset of the
-// tap inside one image relative to the window origin, (c*H*W + (r*dil_h - pad_h)*W + s*dil_w - pad_w)*4,
-// plus the bias (pad_h*W + pad_w)*4 that makes it non-negative; the mask bit of filter row r; the
-// mask bit of filter column s (16 + s); zero.  Padding rows point at the always-set bit 31.
-static std::vector<int32_t> build_tap_table(const Problem &pr)
+// Tap tables of a problem, two ints per row: {byte offset, mask bit of filter row r | mask bit of
+// filter column s (16 + s) << 8}.
+//  - Periodic table [R*S phases][32 rows]: row j of phase ph describes reduction row ph + j of a
+//    step that starts at tap ph of some channel c0: tap (ph + j) % RS of channel c0 + (ph + j) / RS.
+//    Offset = (channel advance*H*W + (r*dil_h - pad_h)*W + s*dil_w - pad_w)*4 + bias, where
+//    bias = (pad_h*W + pad_w)*4 keeps it non-negative; the kernel adds c0*H*W*4.
+//  - Three tail tables [32 rows], for K-steps of 8, 16 and 32: the rows from the start of the last
+//    step of the reduction, with absolute offsets; rows past C*R*S point at the always-set bit 31.
+// Layout of the upload: periodic | tail(8) | tail(16) | tail(32).
+static std::vector<int32_t> build_tap_tables(const Problem &pr)
 {
     const wpk_conv_desc &d = pr.d;
-    std::vector<int32_t> t((size_t)pr.CRSpad * 4, 0);
+    const int RS = d.r * d.s;
     const int bias = (d.pad_h * d.w + d.pad_w) * 4;
-    for (int kk = 0; kk < pr.CRSpad; ++kk) {
-        if (kk < pr.CRS) {
-            int s = kk % d.s, r = (kk / d.s) % d.r, c = kk / (d.s * d.r);
-            t[4 * kk] = (c * d.h * d.w + (r * d.dil_h - d.pad_h) * d.w + s * d.dil_w - d.pad_w) * 4 + bias;
-            t[4 * kk + 1] = r;
-            t[4 * kk + 2] = 16 + s;
-        } else {
-            t[4 * kk] = 0;
-            t[4 * kk + 1] = kPadTapBit;
-            t[4 * kk + 2] = kPadTapBit;
+    auto entry = [&](int c, int rs, int32_t *e) {
+        int r = rs / d.s, s = rs % d.s;
+        e[0] = (c * d.h * d.w + (r * d.dil_h - d.pad_h) * d.w + s * d.dil_w - d.pad_w) * 4 + bias;
+        e[1] = r | (16 + s) << 8;
+    };
+    std::vector<int32_t> t((size_t)(RS + 3) * 32 * 2, 0);
+    for (int ph = 0; ph < RS; ++ph)
+        for (int j = 0; j < 32; ++j) entry((ph + j) / RS, (ph + j) % RS, &t[((size_t)ph * 32 + j) * 2]);
+    const int bks[3] = {8, 16, 32};
+    for (int b = 0; b < 3; ++b) {
+        int k0 = (pr.CRS + bks[b] - 1) / bks[b] * bks[b] - bks[b];  // start of the last step
+        for (int j = 0; j < 32; ++j) {
+            int32_t *e = &t[((size_t)(RS + b) * 32 + j) * 2];
+            int kk = k0 + j;
+            if (kk < pr.CRS) {
+                entry(kk / RS, kk % RS, e);
+            } else {
+                e[0] = 0;
+                e[1] = kPadTapBit | kPadTapBit << 8;
+            }
         }
     }
     return t;
@@ -186,7 +201,7 @@ static std::vector<int32_t> build_tap_table(const Problem &pr)
 
 static int upload_tap_table(const Problem &pr, int32_t **out)
 {
-    std::vector<int32_t> t = build_tap_table(pr);
+    std::vector<int32_t> t = build_tap_tables(pr);
     int32_t *dptr = nullptr;
     WPK_HIP(hipMalloc((void **)&dptr, t.size() * sizeof(int32_t)));
     hipError_t e = hipMemcpy(dptr, t.data(), t.size() * sizeof(int32_t), hipMemcpyHostToDevice);
@@ -245,6 +260,11 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     const wpk_conv_desc &d = pr.d;
     IgemmArgs a;
     a.x = x; a.wp = wp; a.y = y; a.ktab = ktab;
+    a.RS = d.r * d.s;
+    a.HW4 = d.h * d.w * 4;
+    a.bk_div_rs = cfg.bk / a.RS;
+    a.bk_mod_rs = cfg.bk % a.RS;
+    a.ttab = ktab + ((size_t)a.RS + (cfg.bk == 8 ? 0 : cfg.bk == 16 ? 1 : 2)) * 32 * 2;
     a.N = d.n; a.C = d.c; a.H = d.h; a.W = d.w; a.K = d.k; a.P = pr.P; a.Q = pr.Q; a.R = d.r; a.S = d.s;
     a.stride_h = d.stride_h; a.stride_w = d.stride_w; a.pad_h = d.pad_h; a.pad_w = d.pad_w;
     a.dil_h = d.dil_h; a.dil_w = d.dil_w;

@@ -493,12 +493,12 @@ void wpk_tune_default_options(wpk_tune_options *o)
 {
     if (!o) return;
     memset(o, 0, sizeof *o);
-    o->population = 24;
-    o->elites = 4;
-    o->next_population = 24;
-    o->participants = 24;
-    o->max_generations = 12;
-    o->patience = 4;
+    o->population = 48;
+    o->elites = 6;
+    o->next_population = 48;
+    o->participants = 48;
+    o->max_generations = 16;
+    o->patience = 5;
     o->mutation = 0.15;
     o->eps = 0.03;
     o->seed = 2008;

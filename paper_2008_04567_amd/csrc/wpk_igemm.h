@@ -158,26 +158,47 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     constexpr int NW = WL;        // weight quads per thread and tile
     float xr[PD * NX];
     v4f wr[PD * NW];
-    int tap_off[XR], tap_r[XR], tap_s[XR];  // wave-uniform: live in scalar registers
+    int tap_off[XR], tap_rs[XR];  // wave-uniform: live in scalar registers
 
-    // A row group owns XR consecutive reduction rows of the step, so its tap-table entries are
-    // one contiguous, wave-uniform block fetched with scalar loads.
+    // Tap lookup.  Reduction row kk = c*RS + rs.  A step starting at row k0 = c0*RS + phase sees
+    // a pattern of (r, s, channel advance) that depends on phase alone, so a table of RS phases x
+    // 32 rows -- a few KB, resident in the scalar cache -- serves every step; the step's channel
+    // base c0*H*W*4 is added on the scalar unit.  (One table row per reduction row of the whole
+    // problem would miss the scalar cache at every step and stall the wave on its first LDS wait.)
+    // The last step of the reduction is the only one with padding rows past C*R*S; it reads a
+    // separate 32-row table with exact entries.  Steps are visited in increasing order inside a
+    // segment, so (c0, phase) advance incrementally.
+    int tap_cbase = 0;  // channel base of the tile whose taps are loaded, added at the use
+    int tap_c0 = (kbeg * BK) / a.RS;
+    int tap_phase = kbeg * BK - tap_c0 * a.RS;
     auto load_taps = [&](int step) WPK_LAMBDA {
-        tap_ptr tp = taps + 4 * (step * BK + rg * XR);
+        const bool last = step == a.nsteps - 1;
+#ifdef WPK_EXP_HOTTAPS
+        tap_ptr tp = taps + 2 * (rg * XR) + 0 * step;
+#else
+        tap_ptr tp = last ? (tap_ptr)(unsigned long long)a.ttab + 2 * (rg * XR)
+                          : taps + 2 * (tap_phase * 32 + rg * XR);
+#endif
+        tap_cbase = last ? 0 : tap_c0 * a.HW4;
         static_for<XR>([&](auto J) WPK_LAMBDA {
             constexpr int jj = decltype(J)::value;
-            tap_off[jj] = tp[4 * jj];
-            tap_r[jj] = tp[4 * jj + 1];
-            tap_s[jj] = tp[4 * jj + 2];
+            tap_off[jj] = tp[2 * jj];
+            tap_rs[jj] = tp[2 * jj + 1];
         });
+        tap_c0 += a.bk_div_rs;
+        tap_phase += a.bk_mod_rs;
+        if (tap_phase >= a.RS) {
+            tap_phase -= a.RS;
+            tap_c0 += 1;
+        }
     };
     // global -> register set SET: activation dword E of the tile whose taps are loaded
     auto load_x = [&](auto SET, auto E) WPK_LAMBDA {
         constexpr int set = decltype(SET)::value, e = decltype(E)::value, i = e / XR, jj = e % XR;
-        int bad = __builtin_amdgcn_sbfe((int)xinv[i], tap_r[jj], 1) |
-                  __builtin_amdgcn_sbfe((int)xinv[i], tap_s[jj], 1);  // 0 or all ones
+        int bad = __builtin_amdgcn_sbfe((int)xinv[i], tap_rs[jj] & 0xff, 1) |
+                  __builtin_amdgcn_sbfe((int)xinv[i], tap_rs[jj] >> 8, 1);  // 0 or all ones
         xr[set * NX + e] = __builtin_bit_cast(
-            float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, xvoff[i] | bad, tap_off[jj], 0));
+            float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, xvoff[i] | bad, tap_off[jj] + tap_cbase, 0));
     };
     // global -> register set SET: weight quad E of the tile of `step`
     auto load_w = [&](auto SET, int step, auto E) WPK_LAMBDA {
@@ -237,7 +258,6 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
         static_for<NMT>([&](auto J) WPK_LAMBDA {
             bv[decltype(J)::value] = *reinterpret_cast<const v4f *>(xs + decltype(J)::value * 32 * PX);
         });
-        if constexpr (inter) load_taps(kbeg + r + 1 + PD);
         __builtin_amdgcn_sched_barrier(0);
         static_for<BK / 8>([&](auto KO) WPK_LAMBDA {
             constexpr int ko = decltype(KO)::value;
@@ -260,6 +280,15 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                 acc[ij] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[c * NNT + i][q], bv[c * NMT + j][q],
                                                                acc[ij], 0, 0, 0);
                 if constexpr (inter) {
+                    // The scalar loads of the next tile's taps go behind the MFMA that is the last
+                    // to wait for an operand of the first octet: scalar and LDS loads share one
+                    // counter, so the next wait for LDS data also waits for them -- and from here
+                    // that wait is most of an octet of MFMAs away.
+                    if constexpr (t == NNT * NMT - 1) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        load_taps(kbeg + r + 1 + PD);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                     // items [t*NIT/NM, (t+1)*NIT/NM) of the stores-then-loads list ride behind it
                     constexpr int lo = t * NIT / NM, hi = (t + 1) * NIT / NM;
                     static_for<hi - lo>([&](auto D) WPK_LAMBDA {

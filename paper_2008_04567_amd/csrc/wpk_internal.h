@@ -70,10 +70,14 @@ struct IgemmArgs {
     const float *x;
     const float *wp;      // packed weights [CRSpad/4][Kpad][4]
     float *y;
-    const int32_t *ktab;  // [CRSpad][4]: biased byte offset of the tap, mask bit of r, of s, 0
+    const int32_t *ktab;  // periodic tap table [R*S phases][32 rows][2]: byte offset relative to the
+                          // step's channel base (biased); mask bit of r | mask bit of s << 8
+    const int32_t *ttab;  // the same for the 32 rows from the start of the last reduction step, exact
     int32_t N, C, H, W, K, P, Q, R, S;
     int32_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
     int32_t M, PQ, HW, CRS, Kpad;
+    int32_t RS, HW4;               // R*S, H*W*4
+    int32_t bk_div_rs, bk_mod_rs;  // BK / RS, BK % RS
     int32_t nsteps, steps_per_split, split_k;
     int32_t tiles_m, tiles_n, remap;
     int32_t persist;       // 0, or persistent workgroups per compute unit

@@ -220,11 +220,11 @@ def test_engine_matches_oracle_generation_by_generation(seed, fit, cons):
 
 def test_engine_default_sizes_and_flat_fitness():
     opt = B.tune_default_options(seed=3)
-    ref = oga.genetic_search(LO, HI, lambda ch: True, fit_sep, seed=3, pop=24, elites=4, pm=0.15,
-                             eps=0.03, patience=4, max_gen=12)
-    got = B.ga_search(LO, HI, None, fit_sep, opt, history_capacity=12)
+    ref = oga.genetic_search(LO, HI, lambda ch: True, fit_sep, seed=3, pop=48, elites=6, pm=0.15,
+                             eps=0.03, patience=5, max_gen=16)
+    got = B.ga_search(LO, HI, None, fit_sep, opt, history_capacity=16)
     assert got["history"] == ref["history"]
-    flat = B.ga_search(LO, HI, None, lambda ch: 2.0, opt, history_capacity=12)
+    flat = B.ga_search(LO, HI, None, lambda ch: 2.0, opt, history_capacity=16)
     assert flat["generations"] == 1
 
 
@@ -232,7 +232,7 @@ def test_engine_random_mode_and_bad_arguments():
     opt = B.tune_default_options(seed=5, mode=1, max_generations=5, patience=0, eps=0.0)
     got = B.ga_search(LO, HI, None, fit_sep, opt, history_capacity=5)
     assert got["generations"] == 5
-    assert all(len(p) == 24 for p, _ in got["history"])
+    assert all(len(p) == 48 for p, _ in got["history"])
     with pytest.raises(B.WpkError):
         B.ga_search([0, 3], [1, 2], None, fit_sep)       # empty gene range
     with pytest.raises(B.WpkError):
