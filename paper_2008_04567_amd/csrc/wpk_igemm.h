@@ -173,12 +173,8 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     int tap_phase = kbeg * BK - tap_c0 * a.RS;
     auto load_taps = [&](int step) WPK_LAMBDA {
         const bool last = step == a.nsteps - 1;
-#ifdef WPK_EXP_HOTTAPS
-        tap_ptr tp = taps + 2 * (rg * XR) + 0 * step;
-#else
         tap_ptr tp = last ? (tap_ptr)(unsigned long long)a.ttab + 2 * (rg * XR)
                           : taps + 2 * (tap_phase * 32 + rg * XR);
-#endif
         tap_cbase = last ? 0 : tap_c0 * a.HW4;
         static_for<XR>([&](auto J) WPK_LAMBDA {
             constexpr int jj = decltype(J)::value;
@@ -246,6 +242,8 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     // whatever store and load is left done up front.  One barrier per step, at its end.
     constexpr int NM = (BK / 2) * NNT * NMT;       // MFMAs per step and wave
     constexpr int NIT = NXQ + NW + NX + NW;        // stores (x, w) then loads (x, w)
+    // the first load item must not come before the scalar tap loads it depends on
+    static_assert(((NXQ + NW) * NM + NIT - 1) / NIT >= NNT * NMT, "taps are loaded too late");
     auto step_body = [&](const int r, auto SET, auto INTERLEAVE) WPK_LAMBDA {
         constexpr bool inter = decltype(INTERLEAVE)::value;
         const int cur = r & 1;
