@@ -74,6 +74,8 @@ def main():
     ap.add_argument("--tune-mode", type=int, default=0, help="0 genetic, 1 random, 2 exhaustive")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--verbose-tune", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 256 MiB device copy (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (--gpus 1)")
@@ -181,6 +183,13 @@ def main():
                       "tune_seconds": round(t_tune, 1)},
            "pct_fp32_mfma_peak": round(100 * value / FP32_MFMA_PEAK_TFLOPS, 2),
            "roofline": roofline, "layers": rows}
+    if args.calibrate_copy:
+        src = torch.zeros(64 << 20, device=dev, dtype=torch.float32)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log("calibration: 3 device copies of 256 MiB read + 256 MiB written")
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(W, layers)
     plan.destroy()

@@ -153,7 +153,8 @@ static int ensure_device()
     hipDeviceProp_t prop;
     WPK_HIP(hipGetDeviceProperties(&prop, dev));
     g_cus = prop.multiProcessorCount;
-    std::string name = std::string(prop.gcnArchName) + ":" + prop.name;
+    // architecture string and compute-unit count: the marketing name is not stable across tools
+    std::string name = std::string(prop.gcnArchName) + ":cu" + std::to_string(g_cus);
     std::replace(name.begin(), name.end(), ' ', '_');
     set_device_name(name);
     g_dev_ready = true;
