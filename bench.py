@@ -106,9 +106,10 @@ def main():
             hit = B.cache_lookup(d) is not None
             cid, rep = B.conv_tune_ex(d, opt, force=False)
             if not hit:
-                log("tuned %-28s %-28s split %2d remap %d: %8.2f us (default %8.2f us), %d evals, "
-                    "%d gens, %.1f s" % (l["name"], B.config_kernel_name(rep.best), rep.best.split_k,
-                                         rep.best.xcd_remap, rep.best_us, rep.default_us,
+                log("tuned %-28s %-30s split %2d remap %d persist %d: %8.2f us (default %8.2f us), "
+                    "%d evals, %d gens, %.1f s" % (l["name"], B.config_kernel_name(rep.best),
+                                         rep.best.split_k, rep.best.xcd_remap, rep.best.persist,
+                                         rep.best_us, rep.default_us,
                                          rep.evaluations, rep.generations, rep.seconds))
         if args.cache:
             B.cache_save(args.cache)
@@ -162,11 +163,12 @@ def main():
         abytes = 4.0 * (l["n"] * l["c"] * l["h"] * l["w"] + l["k"] * l["c"] * l["r"] * l["s"]
                         + l["n"] * l["k"] * P * Q)
         rows.append({"layer": l["name"], "kernel": B.config_kernel_name(cfg), "split_k": cfg.split_k,
-                     "xcd_remap": cfg.xcd_remap, "us": round(per_layer_us[i], 2),
+                     "xcd_remap": cfg.xcd_remap, "persist": cfg.persist, "stages": cfg.stages,
+                     "us": round(per_layer_us[i], 2),
                      "tflops": round(tf, 2), "pct_fp32_mfma_peak": round(100 * tf / FP32_MFMA_PEAK_TFLOPS, 1),
                      "gbs_algorithmic": round(abytes / (per_layer_us[i] * 1e-6) / 1e9, 1)})
-        log("%-28s %-26s split %2d  %9.2f us  %7.2f TFLOP/s  %5.1f%% of fp32 MFMA peak  %7.1f GB/s"
-            % (l["name"], rows[-1]["kernel"], cfg.split_k, per_layer_us[i], tf,
+        log("%-28s %-30s split %2d persist %d  %9.2f us  %7.2f TFLOP/s  %5.1f%% of fp32 MFMA peak  %7.1f GB/s"
+            % (l["name"], rows[-1]["kernel"], cfg.split_k, cfg.persist, per_layer_us[i], tf,
                rows[-1]["pct_fp32_mfma_peak"], rows[-1]["gbs_algorithmic"]))
     dom = int(np.argmax(per_layer_us))
     dom_tf = flops[dom] / (per_layer_us[dom] * 1e-6) / 1e12
