@@ -21,7 +21,8 @@
  *     it as a non-negative int.  Nothing throws or aborts across this boundary.
  *   - Calls that share a stream are ordered; calls on different streams that use the one-shot
  *     entry points share library scratch (packed weights, lookup tables) and must not overlap.
- *     Plans own their scratch and may run concurrently with each other.
+ *     Plans own their scratch and may run concurrently with each other; the layers of one plan
+ *     share it and must run one after another (one stream, or ordered streams).
  *   - The library never falls back to the CPU: without a usable GPU every compute entry point
  *     returns WPK_E_HIP.
  */

@@ -252,9 +252,35 @@ static int run_ref(const Problem &pr, const float *x, const float *w, float *y, 
     return WPK_OK;
 }
 
+// Device buffer for the fix-up of persistent launches: counters (kept zero between launches) in
+// the first kFixupCounterBytes, partial-tile slots after them.
+struct FixupBuf {
+    char *ptr = nullptr;
+    size_t bytes = 0;
+};
+static int fixup_reserve(FixupBuf &b, size_t bytes)
+{
+    if (bytes <= b.bytes) return WPK_OK;
+    if (b.ptr) WPK_HIP(hipFree(b.ptr));  // synchronises: earlier users are done
+    b.ptr = nullptr;
+    b.bytes = 0;
+    WPK_HIP(hipMalloc((void **)&b.ptr, bytes));
+    WPK_HIP(hipMemset(b.ptr, 0, kFixupCounterBytes));
+    b.bytes = bytes;
+    return WPK_OK;
+}
+static void fixup_release(FixupBuf &b)
+{
+    if (b.ptr) (void)hipFree(b.ptr);
+    b.ptr = nullptr;
+    b.bytes = 0;
+}
+
 // Launch one member of the tiled family.  cfg must be legal for pr (checked by the callers).
+// `fix` is the fix-up workspace of a persistent launch, large enough for fixup_need(); with a
+// NULL workspace shared tiles are accumulated with atomics into zeroed outputs.
 static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32_t *ktab,
-                      const float *x, const float *wp, float *y, hipStream_t st)
+                      const float *x, const float *wp, float *y, const FixupBuf *fix, hipStream_t st)
 {
     int vi = find_variant(cfg.bm, cfg.bn, cfg.bk, cfg.wm, cfg.wn, cfg.stages);
     if (vi < 0) return WPK_E_NO_CONFIG;
@@ -282,10 +308,19 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     a.w_bytes = (uint32_t)((int64_t)pr.CRSpad * pr.Kpad * 4);
     a.persist = cfg.persist;
     a.grid_persist = cfg.persist * (g_cus > 0 ? g_cus : 256);
+    a.ws = nullptr;
+    a.ws_cnt = nullptr;
+    a.ws_maxc = 0;
+    FixupNeed need = fixup_need(pr, cfg, g_cus);
+    if (need.bytes > 0 && fix && fix->ptr && fix->bytes >= (size_t)need.bytes) {
+        a.ws_cnt = (int32_t *)fix->ptr;
+        a.ws = (float *)(fix->ptr + need.slots_offset);
+        a.ws_maxc = (int32_t)need.maxc;
+    }
     if (a.split_k > 1) {
         int rc = zero_fill(y, pr.y_elems, st);
         if (rc != WPK_OK) return rc;
-    } else if (cfg.persist > 0) {
+    } else if (cfg.persist > 0 && !a.ws) {
         // tiles beyond the last whole round are accumulated with atomics: zero their pixels
         int tiles = a.tiles_m * a.tiles_n;
         int tiles_dp = tiles / a.grid_persist * a.grid_persist;
@@ -313,6 +348,7 @@ struct Prepared {
     int32_t *ktab;
 };
 static std::map<std::string, Prepared> g_prepared;
+static FixupBuf g_fixup;
 static float *g_wscratch = nullptr;
 static size_t g_wscratch_elems = 0;
 
@@ -366,7 +402,12 @@ static int fwd_with(const Problem &pr, const wpk_conv_config &cfg, const float *
     if (rc != WPK_OK) return rc;
     rc = pack_weights(pr, w, wp, st);
     if (rc != WPK_OK) return rc;
-    return run_config(pr, cfg, prep->ktab, x, wp, y, st);
+    FixupNeed need = fixup_need(pr, cfg, g_cus);
+    if (need.bytes > 0) {
+        rc = fixup_reserve(g_fixup, (size_t)need.bytes);
+        if (rc != WPK_OK) return rc;
+    }
+    return run_config(pr, cfg, prep->ktab, x, wp, y, &g_fixup, st);
 }
 
 // ---- timing protocol of the tuner ------------------------------------------------------------------
@@ -378,6 +419,7 @@ struct TuneCtx {
     float *x, *w, *wp, *y, *yref, *dref;
     unsigned *err_bits;
     int32_t *ktab;
+    FixupBuf fix;
     int rejected;
     int hip_failed;
     std::map<int, double> times_us;  // config id -> median microseconds
@@ -387,7 +429,13 @@ static int measure_us(TuneCtx &t, const wpk_conv_config &cfg, double *us_out, do
 {
     // one verification launch, compared on the device with the direct kernel's output
     WPK_HIP(hipMemsetAsync(t.err_bits, 0, sizeof(unsigned), t.st));
-    int rc = run_config(t.pr, cfg, t.ktab, t.x, t.wp, t.y, t.st);
+    FixupNeed need = fixup_need(t.pr, cfg, g_cus);
+    if (need.bytes > 0) {
+        WPK_HIP(hipStreamSynchronize(t.st));
+        int rf = fixup_reserve(t.fix, (size_t)need.bytes);
+        if (rf != WPK_OK) return rf;
+    }
+    int rc = run_config(t.pr, cfg, t.ktab, t.x, t.wp, t.y, &t.fix, t.st);
     if (rc != WPK_OK) return rc;
     hipLaunchKernelGGL(compare_kernel, dim3(512), dim3(256), 0, t.st, t.y, t.yref, t.dref,
                        (long long)t.pr.y_elems, t.err_bits);
@@ -406,7 +454,7 @@ static int measure_us(TuneCtx &t, const wpk_conv_config &cfg, double *us_out, do
     auto timed = [&](int launches, double *ms) -> int {
         WPK_HIP(hipEventRecord(t.e0, t.st));
         for (int i = 0; i < launches; ++i) {
-            int r = run_config(t.pr, cfg, t.ktab, t.x, t.wp, t.y, t.st);
+            int r = run_config(t.pr, cfg, t.ktab, t.x, t.wp, t.y, &t.fix, t.st);
             if (r != WPK_OK) return r;
         }
         WPK_HIP(hipEventRecord(t.e1, t.st));
@@ -476,6 +524,7 @@ static void tune_free(TuneCtx &t)
     if (t.dref) (void)hipFree(t.dref);
     if (t.err_bits) (void)hipFree(t.err_bits);
     if (t.ktab) (void)hipFree(t.ktab);
+    fixup_release(t.fix);
     if (t.e0) (void)hipEventDestroy(t.e0);
     if (t.e1) (void)hipEventDestroy(t.e1);
     if (t.st) (void)hipStreamDestroy(t.st);
@@ -523,6 +572,7 @@ struct wpk_plan {
         float *wp;
         bool has_w;
     };
+    FixupBuf fix;  // fix-up workspace shared by the layers (they run one after another)
     std::vector<Layer> layers;
     std::vector<int32_t *> ktabs;  // one per distinct descriptor
 };
@@ -726,6 +776,8 @@ int wpk_conv_plan(const wpk_conv_desc *layers, int32_t n_layers, int32_t tune, w
         hipError_t e = hipMalloc((void **)&L.wp, (size_t)L.pr.CRSpad * L.pr.Kpad * sizeof(float));
         if (e != hipSuccess) { set_last_hip_error((int)e); rc = WPK_E_HIP; break; }
         plan->layers.push_back(L);
+        FixupNeed need = fixup_need(L.pr, L.cfg, g_cus);
+        if (need.bytes > 0) rc = fixup_reserve(plan->fix, (size_t)need.bytes);
     }
     if (rc != WPK_OK) {
         wpk_plan_destroy(plan);
@@ -751,7 +803,7 @@ int wpk_plan_run_layer(wpk_plan *plan, int32_t layer, const float *x, float *y, 
     if (layer < 0 || layer >= (int)plan->layers.size()) return WPK_E_BAD_ARG;
     wpk_plan::Layer &L = plan->layers[layer];
     if (!L.has_w) return WPK_E_BAD_ARG;
-    return run_config(L.pr, L.cfg, plan->ktabs[L.unique], x, L.wp, y, (hipStream_t)stream);
+    return run_config(L.pr, L.cfg, plan->ktabs[L.unique], x, L.wp, y, &plan->fix, (hipStream_t)stream);
 }
 
 int wpk_plan_run(wpk_plan *plan, const float *const *x, float *const *y, void *stream)
@@ -780,6 +832,12 @@ int wpk_plan_set_layer_config(wpk_plan *plan, int32_t layer, const wpk_conv_conf
     if (!plan || !cfg) return WPK_E_NULL_PTR;
     if (layer < 0 || layer >= (int)plan->layers.size()) return WPK_E_BAD_ARG;
     if (!legal_for(plan->layers[layer].pr, *cfg)) return WPK_E_NO_CONFIG;
+    FixupNeed need = fixup_need(plan->layers[layer].pr, *cfg, g_cus);
+    if (need.bytes > (int64_t)plan->fix.bytes) {
+        WPK_HIP(hipDeviceSynchronize());  // the old workspace may still be in use
+        int rc = fixup_reserve(plan->fix, (size_t)need.bytes);
+        if (rc != WPK_OK) return rc;
+    }
     plan->layers[layer].cfg = *cfg;
     return WPK_OK;
 }
@@ -791,6 +849,7 @@ void wpk_plan_destroy(wpk_plan *plan)
         if (L.wp) (void)hipFree(L.wp);
     for (int32_t *t : plan->ktabs)
         if (t) (void)hipFree(t);
+    fixup_release(plan->fix);
     delete plan;
 }
 

@@ -159,6 +159,30 @@ bool legal_for(const Problem &pr, const wpk_conv_config &cfg)
     return true;
 }
 
+// Workspace of the persistent schedule's fix-up: the tiles beyond the last whole round are shared;
+// a tile of nsteps consecutive units cut into runs of at least q units meets at most
+// ceil((nsteps-1)/q) + 1 runs (every run holds one unit when there are fewer units than runs).
+FixupNeed fixup_need(const Problem &pr, const wpk_conv_config &cfg, int compute_units)
+{
+    FixupNeed n = {0, 0, 0, 0};
+    if (cfg.persist <= 0) return n;
+    if (compute_units <= 0) compute_units = 256;
+    int64_t G = (int64_t)cfg.persist * compute_units;
+    int64_t tiles = ((pr.M + cfg.bm - 1) / cfg.bm) * ((pr.d.k + cfg.bn - 1) / cfg.bn);
+    int64_t shared = tiles - tiles / G * G;
+    int64_t nsteps = (pr.CRS + cfg.bk - 1) / cfg.bk;
+    if (shared == 0 || nsteps <= 1) return n;
+    int64_t q = shared * nsteps / G;
+    n.shared_tiles = shared;
+    n.maxc = q > 0 ? std::min<int64_t>(nsteps, (nsteps - 1 + q - 1) / q + 1) : nsteps;
+    // the counters sit in a region of fixed size at the front, so that buffers reused between
+    // configurations never find slot data where counters are expected
+    n.slots_offset = kFixupCounterBytes;
+    n.bytes = n.slots_offset + shared * n.maxc * cfg.bm * cfg.bn * 4;
+    if (shared * 4 > kFixupCounterBytes || n.bytes > kFixupMaxBytes) n = FixupNeed{0, 0, 0, 0};  // use atomics
+    return n;
+}
+
 // Untuned default: smallest estimated time under a crude model -- workgroups are dealt to the
 // compute units in rounds, a workgroup costs its multiply-accumulate count plus a fixed
 // per-step and per-workgroup overhead, small wave tiles pay for their operand re-reads and a

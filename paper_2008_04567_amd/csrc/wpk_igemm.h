@@ -39,6 +39,7 @@ namespace wpk {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 // Lambdas in the kernel must be inlined before the register arrays they capture are split up.
 #define WPK_LAMBDA __attribute__((always_inline))
@@ -113,9 +114,19 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     const int wstep_bytes = (BK / 4) * a.Kpad * 16;  // one reduction step further
     const int wquad_bytes = (T / BN) * a.Kpad * 16;  // this thread's next quad in the same step
 
-    // One segment of work: reduction steps [kbeg, kend) of output tile `tile`, written with plain
-    // stores, or added with atomics when other workgroups hold the rest of the reduction.
-    auto run_segment = [&](const int tile, const int kbeg, const int kend, const bool atomic) WPK_LAMBDA {
+    // One segment of work: reduction steps [kbeg, kend) of output tile `tile`.  How the result
+    // leaves the workgroup (mode):
+    //   kStore  plain stores (the segment is the tile's whole reduction);
+    //   kAtomic fp32 atomics into y, which the host zeroed (fixed reduction slices);
+    //   kFixup  the tile is shared by fix_n workgroups of a persistent launch, this one being
+    //           number fix_slot: each stores its partial tile to its slot of the workspace and
+    //           bumps the tile's arrival counter; whoever arrives last adds up the other slots
+    //           and stores y.  Nobody waits for anybody, y needs no zeroing, and the counter is
+    //           back at zero when the kernel ends.
+    enum { kStore = 0, kAtomic = 1, kFixup = 2 };
+    __shared__ int arrival;
+    auto run_segment = [&](const int tile, const int kbeg, const int kend, const int mode,
+                           const int fix_j, const int fix_slot, const int fix_n) WPK_LAMBDA {
     if (kbeg >= kend) return;  // nothing to reduce: touch neither the tap table nor y
     const int tile_n = tile % a.tiles_n, tile_m = tile / a.tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -337,6 +348,51 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
         step_body(r, std::integral_constant<int, 0>{}, false_type{});
     }
 
+    // ---- fix-up of a shared tile -----------------------------------------------------------------
+    if (mode == kFixup) {
+        // Slot layout: accumulator quad (ij, e4) of thread t at float (ij*4 + e4)*4*T + 4*t.
+        // Partials travel between workgroups that may sit on different XCDs, whose L2 caches do
+        // not snoop each other.  Instead of fences that write back and invalidate whole caches,
+        // the partials alone are stored and loaded with the system-scope cache policy (write
+        // through / read past the non-coherent levels); everything else stays cached.
+        constexpr int kCoherent = 17;  // sc0 | sc1
+        const __amdgpu_buffer_rsrc_t srsrc = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(a.ws + (size_t)fix_j * a.ws_maxc * (BM * BN)), 0, a.ws_maxc * (BM * BN) * 4,
+            0x00020000);
+        const int mine = (fix_slot * (BM * BN) + 4 * tid) * 4;
+        static_for<NNT * NMT * 4>([&](auto Q) WPK_LAMBDA {
+            constexpr int qd = decltype(Q)::value, ij = qd / 4, e4 = qd % 4;
+            v4f v = {acc[ij][4 * e4], acc[ij][4 * e4 + 1], acc[ij][4 * e4 + 2], acc[ij][4 * e4 + 3]};
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), srsrc, mine,
+                                                   qd * 16 * T, kCoherent);
+        });
+        // every store of this wave acknowledged, then every wave of the workgroup, before the
+        // arrival is counted
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (tid == 0) arrival = atomicAdd(a.ws_cnt + fix_j, 1);
+        __syncthreads();
+        const int arrived_before = arrival;
+        __syncthreads();  // everyone has read `arrival` before a later segment overwrites it
+        if (arrived_before != fix_n - 1) return;  // not the last: done with this tile
+        if (tid == 0) a.ws_cnt[fix_j] = 0;        // leave the counter clean for the next launch
+        for (int sl = 0; sl < fix_n; ++sl) {
+            if (sl == fix_slot) continue;
+            const int other = (sl * (BM * BN) + 4 * tid) * 4;
+            static_for<NNT * NMT * 4>([&](auto Q) WPK_LAMBDA {
+                constexpr int qd = decltype(Q)::value, ij = qd / 4, e4 = qd % 4;
+                v4f v = __builtin_bit_cast(
+                    v4f, __builtin_amdgcn_raw_buffer_load_b128(srsrc, other, qd * 16 * T, kCoherent));
+                acc[ij][4 * e4] += v[0];
+                acc[ij][4 * e4 + 1] += v[1];
+                acc[ij][4 * e4 + 2] += v[2];
+                acc[ij][4 * e4 + 3] += v[3];
+            });
+        }
+    }
+    const bool atomic = mode == kAtomic;
+
     // ---- epilogue: D[row = channel][col = pixel]; register e of lane l holds row
     //      8*(e/4) + 4*(l/32) + e%4 and column l%32 of its 32x32 block ---------------------------
     static_for<NMT>([&](auto J) WPK_LAMBDA {
@@ -365,46 +421,57 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
 
     // ---- which segments this workgroup runs ----------------------------------------------------
     // persist == 0: one workgroup per (tile, reduction slice): blockIdx -> tile, slice.
-    // persist  > 0: gridDim.x persistent workgroups.  Each first takes whole tiles g, g+G, ... of
-    //   the first tiles_dp = floor(tiles/G)*G tiles; the steps of the remaining tiles, laid end to
-    //   end, are then cut into G equal runs, one per workgroup, so every workgroup does the same
-    //   number of steps (+-1).  A run that does not cover a tile's whole reduction adds its part
-    //   with atomics into y, which the host has zeroed for those tiles.
+    // persist  > 0: gridDim.x = G persistent workgroups.  Each first takes whole tiles g, g+G, ...
+    //   of the first tiles_dp = floor(tiles/G)*G tiles.  The reduction steps of the remaining
+    //   tiles, laid end to end (`units` of them), are cut into G runs of q or q+1 steps, one per
+    //   workgroup (the first `rem` get q+1), so all do the same amount of work.  A run that does
+    //   not cover a tile's whole reduction shares the tile with its neighbours in g: fix-up
+    //   through the workspace if the host gave one, else atomics into zeroed y.
     const int tiles = a.tiles_m * a.tiles_n;
     const bool persistent = a.persist > 0;
     const int G = gridDim.x, g = blockIdx.x;
     const int tiles_dp = persistent ? tiles / G * G : 0;
     const long long units = (long long)(tiles - tiles_dp) * a.nsteps;
+    const long long q = units / G, rem = units % G;
+    auto run_start = [&](long long gg) { return gg * q + (gg < rem ? gg : rem); };
+    auto owner_of = [&](long long u) {  // which workgroup's run holds unit u
+        if (u < rem * (q + 1)) return (int)(u / (q + 1));
+        return (int)(rem + (u - rem * (q + 1)) / (q > 0 ? q : 1));
+    };
     int next_dp = g;
-    long long u0 = persistent ? units * g / G : 0;
-    const long long u1 = persistent ? units * (g + 1) / G : 0;
+    long long u0 = persistent ? run_start(g) : 0;
+    const long long u1 = persistent ? run_start(g + 1) : 0;
     bool once = !persistent;
     for (;;) {
-        int tile, kbeg, kend;
-        bool atomic;
+        int tile, kbeg, kend, mode = kStore, fix_j = 0, fix_slot = 0, fix_n = 1;
         if (once) {
             once = false;
             int bid = a.remap ? xcd_remap(g, G) : g;
             tile = bid % tiles;
             kbeg = (bid / tiles) * a.steps_per_split;
             kend = min(a.nsteps, kbeg + a.steps_per_split);
-            atomic = a.split_k > 1;
+            mode = a.split_k > 1 ? kAtomic : kStore;
         } else if (persistent && next_dp < tiles_dp) {
             tile = next_dp;
             kbeg = 0;
             kend = a.nsteps;
             next_dp += G;
-            atomic = false;
         } else if (persistent && u0 < u1) {
-            tile = tiles_dp + (int)(u0 / a.nsteps);
-            kbeg = (int)(u0 % a.nsteps);
+            fix_j = (int)(u0 / a.nsteps);
+            tile = tiles_dp + fix_j;
+            kbeg = (int)(u0 - (long long)fix_j * a.nsteps);
             kend = (int)min((long long)a.nsteps, kbeg + (u1 - u0));
             u0 += kend - kbeg;
-            atomic = !(kbeg == 0 && kend == a.nsteps);
+            if (!(kbeg == 0 && kend == a.nsteps)) {
+                const int first = owner_of((long long)fix_j * a.nsteps);
+                fix_n = owner_of((long long)(fix_j + 1) * a.nsteps - 1) - first + 1;
+                fix_slot = g - first;
+                mode = a.ws ? kFixup : kAtomic;
+            }
         } else {
             break;
         }
-        run_segment(tile, kbeg, kend, atomic);
+        run_segment(tile, kbeg, kend, mode, fix_j, fix_slot, fix_n);
     }
 }
 

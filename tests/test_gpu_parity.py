@@ -47,9 +47,11 @@ def test_every_tile_variant_on_a_ragged_shape():
 
 
 def test_persistent_schedule():
-    """Persistent workgroups: whole rounds of tiles stored plainly, the rest accumulated with
-    atomics into zeroed outputs -- on a shape with more tiles than workgroups (several rounds plus
-    a remainder) and on one with fewer (everything split)."""
+    """Persistent workgroups: whole rounds of tiles stored plainly, the tiles of the last partial
+    round cut into equal runs of reduction steps and summed through the fix-up workspace -- on a
+    shape with more tiles than workgroups (several rounds plus a remainder) and on one with fewer
+    (everything split).  Each configuration runs twice: the second launch finds the arrival
+    counters as the first left them."""
     many = W.layer("many_tiles", 6, 12, (60, 64), 40, 3, 1, 1, x_dist="u11", w_dist="u11", seed=78)
     for l in (RAGGED, many):
         desc = B.make_desc(l)
@@ -60,8 +62,9 @@ def test_persistent_schedule():
                 c = B.make_config(bm, bn, bk, wm, wn, persist=persist, stages=1 + persist % 3)
                 assert B.config_legal(desc, c)
                 print(l["name"], c, flush=True)
-                y = PT.run_gpu(l, x, w, cfg=c)
-                PT.assert_close(y, y_ref, d_ref, repr(c))
+                for again in range(2):
+                    y = PT.run_gpu(l, x, w, cfg=c)
+                    PT.assert_close(y, y_ref, d_ref, repr(c) + " launch %d" % again)
 
 
 def test_split_k_and_remap_settings():
