@@ -317,10 +317,10 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
         a.ws = (float *)(fix->ptr + need.slots_offset);
         a.ws_maxc = (int32_t)need.maxc;
     }
-    if (a.split_k > 1) {
+    if (a.split_k > 1 && !a.ws) {
         int rc = zero_fill(y, pr.y_elems, st);
         if (rc != WPK_OK) return rc;
-    } else if (cfg.persist > 0 && !a.ws) {
+    } else if (a.split_k == 1 && cfg.persist > 0 && !a.ws) {
         // tiles beyond the last whole round are accumulated with atomics: zero their pixels
         int tiles = a.tiles_m * a.tiles_n;
         int tiles_dp = tiles / a.grid_persist * a.grid_persist;

@@ -165,21 +165,32 @@ bool legal_for(const Problem &pr, const wpk_conv_config &cfg)
 FixupNeed fixup_need(const Problem &pr, const wpk_conv_config &cfg, int compute_units)
 {
     FixupNeed n = {0, 0, 0, 0};
-    if (cfg.persist <= 0) return n;
     if (compute_units <= 0) compute_units = 256;
-    int64_t G = (int64_t)cfg.persist * compute_units;
     int64_t tiles = ((pr.M + cfg.bm - 1) / cfg.bm) * ((pr.d.k + cfg.bn - 1) / cfg.bn);
-    int64_t shared = tiles - tiles / G * G;
     int64_t nsteps = (pr.CRS + cfg.bk - 1) / cfg.bk;
-    if (shared == 0 || nsteps <= 1) return n;
-    int64_t q = shared * nsteps / G;
-    n.shared_tiles = shared;
-    n.maxc = q > 0 ? std::min<int64_t>(nsteps, (nsteps - 1 + q - 1) / q + 1) : nsteps;
+    if (cfg.persist > 0) {
+        // tiles of the last partial round, their steps dealt in G runs of q or q+1: a tile's
+        // nsteps steps meet at most ceil((nsteps-1)/q)+1 runs, and never more than nsteps
+        int64_t G = (int64_t)cfg.persist * compute_units;
+        int64_t shared = tiles - tiles / G * G;
+        if (shared == 0 || nsteps <= 1) return n;
+        int64_t q = shared * nsteps / G;
+        n.shared_tiles = shared;
+        n.maxc = q > 0 ? std::min<int64_t>(nsteps, (nsteps - 1 + q - 1) / q + 1) : nsteps;
+    } else {
+        // every tile is shared by its non-empty reduction slices
+        int64_t per = (nsteps + cfg.split_k - 1) / cfg.split_k;
+        int64_t slices = (nsteps + per - 1) / per;
+        if (slices <= 1) return n;
+        n.shared_tiles = tiles;
+        n.maxc = slices;
+    }
     // the counters sit in a region of fixed size at the front, so that buffers reused between
     // configurations never find slot data where counters are expected
     n.slots_offset = kFixupCounterBytes;
-    n.bytes = n.slots_offset + shared * n.maxc * cfg.bm * cfg.bn * 4;
-    if (shared * 4 > kFixupCounterBytes || n.bytes > kFixupMaxBytes) n = FixupNeed{0, 0, 0, 0};  // use atomics
+    n.bytes = n.slots_offset + n.shared_tiles * n.maxc * cfg.bm * cfg.bn * 4;
+    if (n.shared_tiles * 4 > kFixupCounterBytes || n.bytes > kFixupMaxBytes)
+        n = FixupNeed{0, 0, 0, 0};  // use atomics
     return n;
 }
 

@@ -117,9 +117,9 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     // One segment of work: reduction steps [kbeg, kend) of output tile `tile`.  How the result
     // leaves the workgroup (mode):
     //   kStore  plain stores (the segment is the tile's whole reduction);
-    //   kAtomic fp32 atomics into y, which the host zeroed (fixed reduction slices);
-    //   kFixup  the tile is shared by fix_n workgroups of a persistent launch, this one being
-    //           number fix_slot: each stores its partial tile to its slot of the workspace and
+    //   kAtomic fp32 atomics into y, which the host zeroed (no workspace given);
+    //   kFixup  the tile is shared by fix_n workgroups (reduction slices, or neighbouring runs
+    //           of a persistent launch), this one being number fix_slot: each stores its partial tile to its slot of the workspace and
     //           bumps the tile's arrival counter; whoever arrives last adds up the other slots
     //           and stores y.  Nobody waits for anybody, y needs no zeroing, and the counter is
     //           back at zero when the kernel ends.
@@ -420,7 +420,8 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     };  // run_segment
 
     // ---- which segments this workgroup runs ----------------------------------------------------
-    // persist == 0: one workgroup per (tile, reduction slice): blockIdx -> tile, slice.
+    // persist == 0: one workgroup per (tile, reduction slice): blockIdx -> tile, slice; the slices
+    //   of a tile meet through the workspace if the host gave one, else through atomics.
     // persist  > 0: gridDim.x = G persistent workgroups.  Each first takes whole tiles g, g+G, ...
     //   of the first tiles_dp = floor(tiles/G)*G tiles.  The reduction steps of the remaining
     //   tiles, laid end to end (`units` of them), are cut into G runs of q or q+1 steps, one per
@@ -450,7 +451,12 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
             tile = bid % tiles;
             kbeg = (bid / tiles) * a.steps_per_split;
             kend = min(a.nsteps, kbeg + a.steps_per_split);
-            mode = a.split_k > 1 ? kAtomic : kStore;
+            if (a.split_k > 1) {
+                mode = a.ws ? kFixup : kAtomic;
+                fix_j = tile;
+                fix_slot = bid / tiles;
+                fix_n = a.split_k;
+            }
         } else if (persistent && next_dp < tiles_dp) {
             tile = next_dp;
             kbeg = 0;

@@ -85,7 +85,7 @@ struct IgemmArgs {
     uint32_t x_bytes;   // size of x
     uint32_t x_bias;    // (pad_h*W + pad_w)*4: added to every tap offset, subtracted from the base
     uint32_t w_bytes;   // size of the packed weights
-    // persistent launches: fix-up workspace (NULL = accumulate with atomics instead)
+    // fix-up workspace of shared tiles (NULL = accumulate with atomics into zeroed y instead)
     float *ws;          // [shared tiles][ws_maxc slots][BM*BN] partial tiles
     int32_t *ws_cnt;    // [shared tiles] arrival counters, zero between launches
     int32_t ws_maxc;    // slots per shared tile
@@ -93,7 +93,7 @@ struct IgemmArgs {
 
 static const int64_t kFixupCounterBytes = 1 << 20;   // room for 262144 shared tiles
 static const int64_t kFixupMaxBytes = (int64_t)1 << 30;  // beyond this, fall back to atomics
-// Fix-up workspace a persistent launch of `cfg` needs: shared tiles, slots per tile, bytes
+// Fix-up workspace a launch of `cfg` needs (split reduction or persistent): shared tiles, slots per tile, bytes
 // (a fixed-size counter region first, then the slots).  All zero when nothing is shared or the
 // workspace would be too large (the launch then accumulates with atomics).
 struct FixupNeed {
