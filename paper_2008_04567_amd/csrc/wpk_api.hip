@@ -704,6 +704,58 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int
         gens = wpk_ga_search(WPK_N_GENES, lo, hi, tune_constraint, tune_fitness, &t, &t.opt,
                              best_genes, &best_f, &evals, nullptr, nullptr, nullptr, 0);
     }
+    if (t.opt.mode != 2 && t.opt.refine > 0 && best_f > 0.0 && !t.hip_failed && gens >= 0) {
+        // one gene of the winner at a time, every other value of it
+        for (int round = 0; round < t.opt.refine; ++round) {
+            bool moved = false;
+            for (int gi = 0; gi < WPK_N_GENES; ++gi) {
+                int32_t cand[WPK_N_GENES];
+                memcpy(cand, best_genes, sizeof cand);
+                for (int32_t v = lo[gi]; v <= hi[gi]; ++v) {
+                    cand[gi] = v;
+                    wpk_conv_config c;
+                    if (v == best_genes[gi] || !tune_constraint(cand, WPK_N_GENES, &t) ||
+                        wpk_config_from_genes(cand, &c) != WPK_OK || t.times_us.count(wpk_config_id(&c)))
+                        continue;
+                    double f = tune_fitness(cand, WPK_N_GENES, &t);
+                    ++evals;
+                    if (f > best_f) {
+                        best_f = f;
+                        best_genes[gi] = v;
+                        moved = true;
+                    }
+                }
+            }
+            if (!moved) break;
+        }
+        // the five fastest so far once more, in groups long enough for the clocks to settle
+        // where they stay under continuous load: neither a lucky sample nor a short burst at
+        // boost clocks must decide
+        std::vector<std::pair<double, int>> order;
+        for (auto &kv : t.times_us) order.push_back({kv.second, kv.first});
+        std::sort(order.begin(), order.end());
+        double again_best = 0;
+        const double group_us = t.opt.min_group_us;
+        const int reps = t.opt.reps;
+        t.opt.min_group_us = std::max(group_us, 4000.0);
+        t.opt.reps = 3;
+        for (size_t i = 0; i < order.size() && i < 5 && !t.hip_failed; ++i) {
+            wpk_conv_config c;
+            int32_t g[WPK_N_GENES];
+            if (wpk_config_from_id(order[i].second, &c) != WPK_OK || wpk_config_to_genes(&c, g) != WPK_OK)
+                continue;
+            double us = 0, err = 0;
+            int r = measure_us(t, c, &us, &err);
+            if (r != WPK_OK) { t.hip_failed = r; break; }
+            if (us > 0.0 && (again_best == 0 || us < again_best)) {
+                again_best = us;
+                memcpy(best_genes, g, sizeof g);
+            }
+        }
+        if (again_best > 0) best_f = 1.0 / again_best;
+        t.opt.min_group_us = group_us;
+        t.opt.reps = reps;
+    }
     int result;
     if (t.hip_failed) {
         result = t.hip_failed;

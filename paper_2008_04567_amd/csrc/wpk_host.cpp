@@ -541,6 +541,7 @@ void wpk_tune_default_options(wpk_tune_options *o)
     o->min_group_us = 200.0;
     o->mode = 0;
     o->verbose = 0;
+    o->refine = 2;
 }
 
 int wpk_ga_search(int32_t n_genes, const int32_t *lo, const int32_t *hi,
