@@ -37,6 +37,8 @@ def workload_layers(W, name):
         return W.resnet50_stack(1), "config5: ResNet-50 conv stack (53 layers), N=1"
     if name == "resnet50_n16":
         return W.resnet50_stack(16), "config5: ResNet-50 conv stack (53 layers), N=16"
+    if name == "resnet18_n1":
+        return W.resnet18_stack(1), "ResNet-18 conv stack (20 layers), N=1"
     if name == "table1":
         return W.table1_convs(), "Table 1 production layers, N=1"
     raise SystemExit("unknown workload " + name)

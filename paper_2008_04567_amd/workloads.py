@@ -116,6 +116,26 @@ def table1_convs(n=1):
             for i, (nm, h, w, c, k, st) in enumerate(rows)]
 
 
+def resnet18_stack(n=1):
+    """Every convolution of a ResNet-18 (basic blocks), the network of Section 3.1, at the
+    224x224 input size: stem 7x7/2 to 64; max-pool to 56; stages of [2,2,2,2] blocks of two 3x3
+    layers with widths 64/128/256/512; the first 3x3 of stages 2-4 has stride 2 and that block
+    has a 1x1 stride-2 projection shortcut.  20 layers."""
+    out = [layer("stem", n, 3, 224, 64, 7, 2, 3, x_dist="u11", seed=7000)]
+    cin, hw, idx = 64, 56, 1
+    for stage, width in enumerate([64, 128, 256, 512]):
+        for b in range(2):
+            stride = 2 if (b == 0 and stage > 0) else 1
+            tag = "s%db%d" % (stage + 1, b)
+            out.append(layer(tag + ".c1", n, cin, hw, width, 3, stride, 1, seed=7000 + idx)); idx += 1
+            hw_out = hw // stride
+            out.append(layer(tag + ".c2", n, width, hw_out, width, 3, 1, 1, seed=7000 + idx)); idx += 1
+            if stride == 2:
+                out.append(layer(tag + ".proj", n, cin, hw, width, 1, 2, 0, seed=7000 + idx)); idx += 1
+            cin, hw = width, hw_out
+    return out
+
+
 def unique_layers(layers):
     """Layers de-duplicated by shape (Section 3.1: same input/output shape, filter size,
     stride and padding means computationally identical), with multiplicities in ``count``."""

@@ -121,6 +121,22 @@ def test_shape_sweep_default_and_fixed_configs(row):
             PT.assert_close(PT.run_gpu(l, x, w, cfg=c_), y_ref, d_ref, name + repr(c_))
 
 
+@pytest.mark.parametrize("layer", W.table1_convs() + W.unique_layers(W.resnet18_stack(1)),
+                         ids=lambda l: l["name"])
+def test_section3_workloads(layer):
+    """The shapes the paper's Section 3 measures: Table 1's non-square, unpadded production
+    layers and the distinct layers of ResNet-18 at batch 1 -- default configuration, then one
+    split and one persistent member of the family where legal."""
+    x, w = W.make_inputs(layer)
+    y_ref, d_ref = PT.oracle_full(layer, x, w)
+    desc = B.make_desc(layer)
+    PT.assert_close(PT.run_gpu(layer, x, w), y_ref, d_ref, layer["name"] + " default")
+    for c in [B.make_config(64, 64, 16, 2, 2, 4), B.make_config(128, 32, 32, 4, 1, persist=2)]:
+        if B.config_legal(desc, c):
+            print(layer["name"], c, flush=True)
+            PT.assert_close(PT.run_gpu(layer, x, w, cfg=c), y_ref, d_ref, layer["name"] + repr(c))
+
+
 def test_oversized_filter_uses_the_direct_kernel():
     # the tiled family tracks at most 16 filter rows and 15 filter columns per pixel
     for rs in [(17, 2), (2, 16)]:
