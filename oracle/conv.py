@@ -107,3 +107,30 @@ def conv2d_sampled(shape, x, w, flat_idx):
     if rc != 0:
         raise ValueError("oracle rejected the call (rc=%d)" % rc)
     return y, d
+
+
+def conv2d_fused(shape, x, w, bias=None, residual=None, relu=False, threads=0):
+    """The fused operator of Section 2.1 (operator fusion: the sub-graph convolution -> per-channel
+    bias -> element-wise addition of a second tensor -> rectifier computed as one operator), written
+    out as its definition on top of the seven-loop convolution:
+
+        z[n][k][p][q] = conv(x, w)[n][k][p][q] + bias[k] + residual[n][k][p][q]
+        y = max(z, 0) if relu else z
+
+    all in fp64; absent terms are zero.  Returns ``(y64, dnorm)`` where dnorm adds |bias| and
+    |residual| to the convolution's normaliser: the sum of the magnitudes of everything added
+    into an output, which bounds the rounding error of any summation order (the rectifier does
+    not increase a difference)."""
+    y, d, _ = conv2d(shape, x, w, threads=threads)
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float32).astype(np.float64)
+        assert b.shape == (shape.k,), "bias has one entry per output channel"
+        y = y + b[None, :, None, None]
+        d = d + np.abs(b)[None, :, None, None]
+    if residual is not None:
+        r = np.asarray(residual, dtype=np.float32).astype(np.float64).reshape(y.shape)
+        y = y + r
+        d = d + np.abs(r)
+    if relu:
+        y = np.where(y > 0.0, y, 0.0)
+    return y, d

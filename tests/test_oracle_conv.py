@@ -313,3 +313,63 @@ def test_planted_mistakes_are_caught():
     if oc.out_shape(sh2) == oc.out_shape(sh):
         y_pad, _, _ = oc.conv2d(sh2, x, w)
         assert np.max(np.abs(y - y_pad)) > 1e-3
+
+
+# ---- fused operator (Section 2.1, operator fusion) ---------------------------------------------
+def _read_blocks(path):
+    blocks, cur = {}, None
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        if line[0].isalpha():
+            cur = line
+            blocks[cur] = []
+        else:
+            blocks[cur].append([float(v) for v in line.split()])
+    return {k: np.array(v) for k, v in blocks.items()}
+
+
+def test_fused_hand_worked_sample(golden_dir):
+    conv_fix = _read_blocks(os.path.join(golden_dir, "sample_3x3_worked.txt"))
+    fix = _read_blocks(os.path.join(golden_dir, "fused_worked.txt"))
+    assert np.array_equal(fix["conv"], conv_fix["out"])
+    sh = oc.make_shape(1, 1, 3, 3, 1, 3, 3, pad=(1, 1))
+    x, w = conv_fix["in"].reshape(1, 1, 3, 3), conv_fix["filter"].reshape(1, 1, 3, 3)
+    bias = fix["bias"].reshape(1)
+    y, d = oc.conv2d_fused(sh, x, w, bias=bias, residual=fix["residual"], relu=True)
+    assert np.array_equal(y.reshape(3, 3), fix["out"])
+    z, _ = oc.conv2d_fused(sh, x, w, bias=bias, residual=fix["residual"], relu=False)
+    assert np.array_equal(z.reshape(3, 3), fix["z"])
+
+
+def test_fused_special_cases():
+    rng = np.random.default_rng(11)
+    sh = oc.make_shape(2, 3, 6, 5, 4, 3, 2, stride=(1, 2), pad=(1, 0))
+    P, Q = oc.out_shape(sh)
+    x = rng.uniform(-1, 1, (2, 3, 6, 5)).astype(np.float32)
+    w = rng.uniform(-1, 1, (4, 3, 3, 2)).astype(np.float32)
+    b = rng.uniform(-1, 1, 4).astype(np.float32)
+    r = rng.uniform(-1, 1, (2, 4, P, Q)).astype(np.float32)
+    y0, d0, _ = oc.conv2d(sh, x, w)
+    # nothing fused: the plain convolution and its normaliser
+    y, d = oc.conv2d_fused(sh, x, w)
+    assert np.array_equal(y, y0) and np.array_equal(d, d0)
+    # zero weights: what remains is the rectified sum of bias and residual, channel by channel
+    y, d = oc.conv2d_fused(sh, x, np.zeros_like(w), bias=b, residual=r, relu=True)
+    for k in range(4):
+        assert np.array_equal(y[:, k], np.maximum(r[:, k].astype(np.float64) + np.float64(b[k]), 0.0))
+        assert np.array_equal(d[:, k], np.abs(r[:, k].astype(np.float64)) + abs(np.float64(b[k])))
+    # the bias lands on the channel axis, not on a spatial one: a one-hot bias changes one channel
+    onehot = np.zeros(4, np.float32)
+    onehot[2] = 5.0
+    y, _ = oc.conv2d_fused(sh, x, w, bias=onehot)
+    diff = y - y0
+    assert np.allclose(diff[:, 2], 5.0, rtol=0, atol=1e-12) and np.all(np.delete(diff, 2, axis=1) == 0.0)
+    # rectifier: max(z,0) = (z + |z|)/2, and the negative part is removed, not mirrored
+    z, _ = oc.conv2d_fused(sh, x, w, bias=b, residual=r)
+    y, _ = oc.conv2d_fused(sh, x, w, bias=b, residual=r, relu=True)
+    assert np.allclose(y, 0.5 * (z + np.abs(z)), rtol=0, atol=1e-15)
+    assert y.min() == 0.0 and (z < 0).any() and np.array_equal(y[z > 0], z[z > 0])
+    # residual addition commutes with the convolution's linearity: conv(x,w)+r == fused(r)
+    assert np.array_equal(z, y0 + b.astype(np.float64)[None, :, None, None] + r.astype(np.float64))
