@@ -125,6 +125,24 @@ int wpk_conv2d_fwd(const wpk_conv_desc *d, const float *x, const float *w, float
 int wpk_conv2d_fwd_config(const wpk_conv_desc *d, const wpk_conv_config *cfg, const float *x,
                           const float *w, float *y, void *stream);
 
+/*
+ * The fused operator (Section 2.1, operator fusion: a sub-graph computed by one kernel so that
+ * the intermediate tensors never travel through memory):
+ *     y[n][k][p][q] = act( conv(x, w)[n][k][p][q] + bias[k] + residual[n][k][p][q] ),
+ * act = max(., 0) if relu != 0, else the identity.  bias ([K]) and residual (laid out like y)
+ * are DEVICE pointers and may each be NULL (term absent); residual must not overlap y.  The
+ * epilogue is applied by the workgroup that stores the output; only where a launch has to
+ * accumulate with atomics (no workspace large enough) or uses the direct kernel does it follow
+ * as a second launch.  Errors as wpk_conv2d_fwd.
+ */
+int wpk_conv2d_fwd_fused(const wpk_conv_desc *d, const float *x, const float *w, const float *bias,
+                         const float *residual, int32_t relu, float *y, void *stream);
+
+/* Same with an explicit configuration (WPK_E_NO_CONFIG if illegal for d). */
+int wpk_conv2d_fwd_fused_config(const wpk_conv_desc *d, const wpk_conv_config *cfg, const float *x,
+                                const float *w, const float *bias, const float *residual,
+                                int32_t relu, float *y, void *stream);
+
 /* Plain one-output-per-lane direct kernel (no MFMA, no LDS, 64-bit indexing).  The on-device
  * reference the tuner vets candidates against; also serves shapes the tiled family rejects. */
 int wpk_conv2d_ref(const wpk_conv_desc *d, const float *x, const float *w, float *y, void *stream);
@@ -213,17 +231,37 @@ int wpk_conv_plan(const wpk_conv_desc *layers, int32_t n_layers, int32_t tune, w
 int wpk_plan_set_weights(wpk_plan *plan, int32_t layer, const float *w, void *stream);
 
 /* Run every layer in order on `stream`: y[i] = conv(x[i], weights of layer i).  x and y are HOST
- * arrays of n_layers DEVICE pointers.  Weights of every layer must have been set. */
+ * arrays of n_layers DEVICE pointers.  Weights of every layer must have been set.  A layer with
+ * an epilogue (wpk_plan_set_epilogue) applies it. */
 int wpk_plan_run(wpk_plan *plan, const float *const *x, float *const *y, void *stream);
 
 /* Run one layer of the plan. */
 int wpk_plan_run_layer(wpk_plan *plan, int32_t layer, const float *x, float *y, void *stream);
+
+/* Give layer `layer` a fused epilogue (see wpk_conv2d_fwd_fused): `bias` is a DEVICE pointer to K
+ * floats, copied into the plan on `stream` (NULL: no bias); relu != 0 adds the rectifier.  Every
+ * later run of the layer, fused or not, applies it. */
+int wpk_plan_set_epilogue(wpk_plan *plan, int32_t layer, const float *bias, int32_t relu, void *stream);
+
+/* Like wpk_plan_run_layer / wpk_plan_run with a residual tensor added before the rectifier:
+ * `residual` is a DEVICE pointer laid out like y (NULL: none); for the whole plan a HOST array of
+ * n_layers such pointers (the array itself, or any entry, may be NULL). */
+int wpk_plan_run_layer_fused(wpk_plan *plan, int32_t layer, const float *x, const float *residual,
+                             float *y, void *stream);
+int wpk_plan_run_fused(wpk_plan *plan, const float *const *x, const float *const *residual,
+                       float *const *y, void *stream);
 
 int wpk_plan_num_layers(const wpk_plan *plan);
 int wpk_plan_num_unique(const wpk_plan *plan);                       /* distinct descriptors     */
 int wpk_plan_layer_config(const wpk_plan *plan, int32_t layer, wpk_conv_config *out);
 int wpk_plan_set_layer_config(wpk_plan *plan, int32_t layer, const wpk_conv_config *cfg);
 void wpk_plan_destroy(wpk_plan *plan);
+
+/* Cap, in bytes, on the device workspace a launch may use to sum the partial tiles of split and
+ * persistent schedules (default 1 GiB).  A launch that would need more accumulates with fp32
+ * atomics into zeroed outputs instead (one more launch; a fused epilogue then follows as another).
+ * 0 turns the workspace off.  Applies to launches prepared afterwards; WPK_E_BAD_ARG if negative. */
+int wpk_set_workspace_limit(int64_t bytes);
 
 /* ---- introspection used by the benchmark ----------------------------------------------------- */
 /* Name of the device kernel a config launches (static storage), e.g. "wpk_igemm_128x64x16_2x2_p2". */

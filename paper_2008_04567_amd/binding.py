@@ -103,6 +103,9 @@ def lib():
             "wpk_conv2d_fwd": (I, [P(ConvDesc), V, V, V, V]),
             "wpk_conv2d_fwd_config": (I, [P(ConvDesc), P(ConvConfig), V, V, V, V]),
             "wpk_conv2d_ref": (I, [P(ConvDesc), V, V, V, V]),
+            "wpk_conv2d_fwd_fused": (I, [P(ConvDesc), V, V, V, V, ctypes.c_int32, V, V]),
+            "wpk_conv2d_fwd_fused_config": (I, [P(ConvDesc), P(ConvConfig), V, V, V, V, ctypes.c_int32,
+                                                V, V]),
             "wpk_tune_default_options": (None, [P(TuneOptions)]),
             "wpk_conv_tune": (I, [P(ConvDesc)]),
             "wpk_conv_tune_ex": (I, [P(ConvDesc), P(TuneOptions), I, P(TuneReport)]),
@@ -119,6 +122,9 @@ def lib():
             "wpk_plan_set_weights": (I, [V, ctypes.c_int32, V, V]),
             "wpk_plan_run": (I, [V, P(V), P(V), V]),
             "wpk_plan_run_layer": (I, [V, ctypes.c_int32, V, V, V]),
+            "wpk_plan_set_epilogue": (I, [V, ctypes.c_int32, V, ctypes.c_int32, V]),
+            "wpk_plan_run_layer_fused": (I, [V, ctypes.c_int32, V, V, V, V]),
+            "wpk_plan_run_fused": (I, [V, P(V), P(V), P(V), V]),
             "wpk_plan_num_layers": (I, [V]),
             "wpk_plan_num_unique": (I, [V]),
             "wpk_plan_layer_config": (I, [V, ctypes.c_int32, P(ConvConfig)]),
@@ -127,6 +133,7 @@ def lib():
             "wpk_config_kernel_name": (ctypes.c_char_p, [P(ConvConfig)]),
             "wpk_device_info": (I, [ctypes.c_char_p, ctypes.c_int32, i32p]),
             "wpk_version": (ctypes.c_char_p, []),
+            "wpk_set_workspace_limit": (I, [ctypes.c_int64]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -351,6 +358,19 @@ def ga_search(lo, hi, constraint, fitness, options=None, history_capacity=0):
             "generations": gens, "history": history}
 
 
+def conv2d_fwd_fused(desc, x, w, y, bias=None, residual=None, relu=False, cfg=None, stream=None):
+    """y = act(conv(x, w) + bias[k] + residual); with ``cfg`` through that configuration."""
+    if cfg is None:
+        _check(lib().wpk_conv2d_fwd_fused(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(bias),
+                                          _ptr(residual), 1 if relu else 0, _ptr(y), _stream(stream)),
+               "wpk_conv2d_fwd_fused")
+    else:
+        _check(lib().wpk_conv2d_fwd_fused_config(ctypes.byref(desc), ctypes.byref(cfg), _ptr(x), _ptr(w),
+                                                 _ptr(bias), _ptr(residual), 1 if relu else 0,
+                                                 _ptr(y), _stream(stream)),
+               "wpk_conv2d_fwd_fused_config")
+
+
 class Plan:
     """Owner of a ``wpk_plan*``."""
 
@@ -379,6 +399,23 @@ class Plan:
         _check(lib().wpk_plan_run_layer(self.handle, layer, _ptr(x), _ptr(y), _stream(stream)),
                "wpk_plan_run_layer")
 
+    def set_epilogue(self, layer, bias=None, relu=False, stream=None):
+        _check(lib().wpk_plan_set_epilogue(self.handle, layer, _ptr(bias), 1 if relu else 0,
+                                           _stream(stream)), "wpk_plan_set_epilogue")
+
+    def run_layer_fused(self, layer, x, residual, y, stream=None):
+        _check(lib().wpk_plan_run_layer_fused(self.handle, layer, _ptr(x), _ptr(residual), _ptr(y),
+                                              _stream(stream)), "wpk_plan_run_layer_fused")
+
+    def residual_array(self, rs):
+        """Host array of device pointers (None entries allowed) for run_fused()."""
+        return (ctypes.c_void_p * self.n)(*[None if t is None else
+                                            (t.data_ptr() if hasattr(t, "data_ptr") else int(t))
+                                            for t in rs])
+
+    def run_fused(self, xa, ra, ya, stream=None):
+        _check(lib().wpk_plan_run_fused(self.handle, xa, ra, ya, _stream(stream)), "wpk_plan_run_fused")
+
     def num_layers(self):
         return lib().wpk_plan_num_layers(self.handle)
 
@@ -405,6 +442,10 @@ class Plan:
             self.destroy()
         except Exception:
             pass
+
+
+def set_workspace_limit(nbytes):
+    _check(lib().wpk_set_workspace_limit(int(nbytes)), "wpk_set_workspace_limit")
 
 
 def device_info():

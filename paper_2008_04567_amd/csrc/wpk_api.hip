@@ -115,6 +115,21 @@ __global__ void zero_pixels_kernel(float *__restrict__ y, int m_begin, int M, in
     }
 }
 
+// y = act(y + bias[k] + res): the fused epilogue as a pass of its own, for the launches that
+// cannot apply it while storing (atomic accumulation, the direct kernel).
+__global__ void epilogue_kernel(float *__restrict__ y, const float *__restrict__ bias,
+                                const float *__restrict__ res, int relu, int K, int PQ, long long total)
+{
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (long long)gridDim.x * blockDim.x) {
+        float v = y[i];
+        if (bias) v += bias[(i / PQ) % K];
+        if (res) v += res[i];
+        if (relu) v = fmaxf(v, 0.0f);
+        y[i] = v;
+    }
+}
+
 // Synthetic operands for the tuner: value = lo + (hi-lo) * hash(index, seed) / 2^24.
 __global__ void fill_hash_kernel(float *__restrict__ p, long long n, unsigned seed, float lo, float hi)
 {
@@ -252,6 +267,16 @@ static int run_ref(const Problem &pr, const float *x, const float *w, float *y, 
     return WPK_OK;
 }
 
+static int run_epilogue(const Problem &pr, const Epilogue &epi, float *y, hipStream_t st)
+{
+    if (!epi.any()) return WPK_OK;
+    int blocks = (int)std::min<int64_t>(4096, (pr.y_elems + 255) / 256);
+    hipLaunchKernelGGL(epilogue_kernel, dim3(blocks), dim3(256), 0, st, y, epi.bias, epi.res, epi.relu,
+                       pr.d.k, pr.P * pr.Q, (long long)pr.y_elems);
+    WPK_HIP(hipGetLastError());
+    return WPK_OK;
+}
+
 // Device buffer for the fix-up of persistent launches: counters (kept zero between launches) in
 // the first kFixupCounterBytes, partial-tile slots after them.
 struct FixupBuf {
@@ -280,7 +305,8 @@ static void fixup_release(FixupBuf &b)
 // `fix` is the fix-up workspace of a persistent launch, large enough for fixup_need(); with a
 // NULL workspace shared tiles are accumulated with atomics into zeroed outputs.
 static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32_t *ktab,
-                      const float *x, const float *wp, float *y, const FixupBuf *fix, hipStream_t st)
+                      const float *x, const float *wp, float *y, const FixupBuf *fix, hipStream_t st,
+                      const Epilogue &epi = Epilogue())
 {
     int vi = find_variant(cfg.bm, cfg.bn, cfg.bk, cfg.wm, cfg.wn, cfg.stages);
     if (vi < 0) return WPK_E_NO_CONFIG;
@@ -317,6 +343,12 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
         a.ws = (float *)(fix->ptr + need.slots_offset);
         a.ws_maxc = (int32_t)need.maxc;
     }
+    // with atomics into y nobody holds a finished output: the epilogue follows as its own pass
+    const bool shared_by_atomics =
+        !a.ws && (a.split_k > 1 || (cfg.persist > 0 && (a.tiles_m * a.tiles_n) % a.grid_persist != 0));
+    a.bias = shared_by_atomics ? nullptr : epi.bias;
+    a.res = shared_by_atomics ? nullptr : epi.res;
+    a.relu = shared_by_atomics ? 0 : epi.relu;
     if (a.split_k > 1 && !a.ws) {
         int rc = zero_fill(y, pr.y_elems, st);
         if (rc != WPK_OK) return rc;
@@ -339,6 +371,7 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
         }
     }
     WPK_HIP(kLaunch[vi](a, st));
+    if (shared_by_atomics) return run_epilogue(pr, epi, y, st);
     return WPK_OK;
 }
 
@@ -389,7 +422,7 @@ static int check_io(const wpk_conv_desc *d, const void *x, const void *w, const 
 }
 
 static int fwd_with(const Problem &pr, const wpk_conv_config &cfg, const float *x, const float *w,
-                    float *y, hipStream_t st)
+                    float *y, hipStream_t st, const Epilogue &epi = Epilogue())
 {
     std::lock_guard<std::mutex> g(g_mu);
     int rc = ensure_device();
@@ -407,7 +440,7 @@ static int fwd_with(const Problem &pr, const wpk_conv_config &cfg, const float *
         rc = fixup_reserve(g_fixup, (size_t)need.bytes);
         if (rc != WPK_OK) return rc;
     }
-    return run_config(pr, cfg, prep->ktab, x, wp, y, &g_fixup, st);
+    return run_config(pr, cfg, prep->ktab, x, wp, y, &g_fixup, st, epi);
 }
 
 // ---- timing protocol of the tuner ------------------------------------------------------------------
@@ -571,6 +604,8 @@ struct wpk_plan {
         int unique;
         float *wp;
         bool has_w;
+        float *bias;  // library-owned copy of the layer's bias, or NULL
+        int relu;
     };
     FixupBuf fix;  // fix-up workspace shared by the layers (they run one after another)
     std::vector<Layer> layers;
@@ -636,6 +671,46 @@ int wpk_conv2d_fwd(const wpk_conv_desc *d, const float *x, const float *w, float
     wpk_conv_config cfg;
     if (wpk_cache_lookup(d, &cfg) != 1 || !legal_for(pr, cfg)) default_config(pr, g_cus, &cfg);
     return fwd_with(pr, cfg, x, w, y, (hipStream_t)stream);
+}
+
+static int fwd_fused(const wpk_conv_desc *d, const wpk_conv_config *cfg_in, const float *x,
+                     const float *w, const Epilogue &epi, float *y, hipStream_t st)
+{
+    Problem pr;
+    int rc = check_io(d, x, w, y, &pr);
+    if (rc != WPK_OK) return rc;
+    if (cfg_in && !legal_for(pr, *cfg_in)) return WPK_E_NO_CONFIG;
+    if (!pr.tiled_ok) {
+        rc = run_ref(pr, x, w, y, nullptr, st);
+        return rc != WPK_OK ? rc : run_epilogue(pr, epi, y, st);
+    }
+    {
+        std::lock_guard<std::mutex> g(g_mu);
+        rc = ensure_device();
+        if (rc != WPK_OK) return rc;
+    }
+    wpk_conv_config cfg;
+    if (cfg_in) cfg = *cfg_in;
+    else if (wpk_cache_lookup(d, &cfg) != 1 || !legal_for(pr, cfg)) default_config(pr, g_cus, &cfg);
+    return fwd_with(pr, cfg, x, w, y, st, epi);
+}
+
+int wpk_conv2d_fwd_fused(const wpk_conv_desc *d, const float *x, const float *w, const float *bias,
+                         const float *residual, int32_t relu, float *y, void *stream)
+{
+    Epilogue epi;
+    epi.bias = bias; epi.res = residual; epi.relu = relu != 0;
+    return fwd_fused(d, nullptr, x, w, epi, y, (hipStream_t)stream);
+}
+
+int wpk_conv2d_fwd_fused_config(const wpk_conv_desc *d, const wpk_conv_config *cfg, const float *x,
+                                const float *w, const float *bias, const float *residual,
+                                int32_t relu, float *y, void *stream)
+{
+    if (!cfg) return WPK_E_NULL_PTR;
+    Epilogue epi;
+    epi.bias = bias; epi.res = residual; epi.relu = relu != 0;
+    return fwd_fused(d, cfg, x, w, epi, y, (hipStream_t)stream);
 }
 
 int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int force,
@@ -809,6 +884,8 @@ int wpk_conv_plan(const wpk_conv_desc *layers, int32_t n_layers, int32_t tune, w
         if (!L.pr.tiled_ok) { rc = WPK_E_UNSUPPORTED; break; }
         L.wp = nullptr;
         L.has_w = false;
+        L.bias = nullptr;
+        L.relu = 0;
         std::string key = desc_key(&layers[i]);
         auto it = seen.find(key);
         if (it == seen.end()) {
@@ -849,23 +926,56 @@ int wpk_plan_set_weights(wpk_plan *plan, int32_t layer, const float *w, void *st
     return rc;
 }
 
-int wpk_plan_run_layer(wpk_plan *plan, int32_t layer, const float *x, float *y, void *stream)
+int wpk_plan_set_epilogue(wpk_plan *plan, int32_t layer, const float *bias, int32_t relu, void *stream)
+{
+    if (!plan) return WPK_E_NULL_PTR;
+    if (layer < 0 || layer >= (int)plan->layers.size()) return WPK_E_BAD_ARG;
+    wpk_plan::Layer &L = plan->layers[layer];
+    if (bias) {
+        if (!L.bias) WPK_HIP(hipMalloc((void **)&L.bias, (size_t)L.pr.d.k * 4));
+        WPK_HIP(hipMemcpyAsync(L.bias, bias, (size_t)L.pr.d.k * 4, hipMemcpyDeviceToDevice,
+                               (hipStream_t)stream));
+    } else if (L.bias) {
+        WPK_HIP(hipFree(L.bias));  // synchronises: no launch still reads it
+        L.bias = nullptr;
+    }
+    L.relu = relu != 0;
+    return WPK_OK;
+}
+
+int wpk_plan_run_layer_fused(wpk_plan *plan, int32_t layer, const float *x, const float *residual,
+                             float *y, void *stream)
 {
     if (!plan || !x || !y) return WPK_E_NULL_PTR;
     if (layer < 0 || layer >= (int)plan->layers.size()) return WPK_E_BAD_ARG;
     wpk_plan::Layer &L = plan->layers[layer];
     if (!L.has_w) return WPK_E_BAD_ARG;
-    return run_config(L.pr, L.cfg, plan->ktabs[L.unique], x, L.wp, y, &plan->fix, (hipStream_t)stream);
+    Epilogue epi;
+    epi.bias = L.bias; epi.res = residual; epi.relu = L.relu;
+    return run_config(L.pr, L.cfg, plan->ktabs[L.unique], x, L.wp, y, &plan->fix, (hipStream_t)stream,
+                      epi);
+}
+
+int wpk_plan_run_layer(wpk_plan *plan, int32_t layer, const float *x, float *y, void *stream)
+{
+    return wpk_plan_run_layer_fused(plan, layer, x, nullptr, y, stream);
+}
+
+int wpk_plan_run_fused(wpk_plan *plan, const float *const *x, const float *const *residual,
+                       float *const *y, void *stream)
+{
+    if (!plan || !x || !y) return WPK_E_NULL_PTR;
+    for (size_t i = 0; i < plan->layers.size(); ++i) {
+        int rc = wpk_plan_run_layer_fused(plan, (int32_t)i, x[i], residual ? residual[i] : nullptr,
+                                          y[i], stream);
+        if (rc != WPK_OK) return rc;
+    }
+    return WPK_OK;
 }
 
 int wpk_plan_run(wpk_plan *plan, const float *const *x, float *const *y, void *stream)
 {
-    if (!plan || !x || !y) return WPK_E_NULL_PTR;
-    for (size_t i = 0; i < plan->layers.size(); ++i) {
-        int rc = wpk_plan_run_layer(plan, (int32_t)i, x[i], y[i], stream);
-        if (rc != WPK_OK) return rc;
-    }
-    return WPK_OK;
+    return wpk_plan_run_fused(plan, x, nullptr, y, stream);
 }
 
 int wpk_plan_num_layers(const wpk_plan *plan) { return plan ? (int)plan->layers.size() : WPK_E_NULL_PTR; }
@@ -897,8 +1007,10 @@ int wpk_plan_set_layer_config(wpk_plan *plan, int32_t layer, const wpk_conv_conf
 void wpk_plan_destroy(wpk_plan *plan)
 {
     if (!plan) return;
-    for (auto &L : plan->layers)
+    for (auto &L : plan->layers) {
         if (L.wp) (void)hipFree(L.wp);
+        if (L.bias) (void)hipFree(L.bias);
+    }
     for (int32_t *t : plan->ktabs)
         if (t) (void)hipFree(t);
     fixup_release(plan->fix);

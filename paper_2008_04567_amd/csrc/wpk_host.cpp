@@ -162,6 +162,8 @@ bool legal_for(const Problem &pr, const wpk_conv_config &cfg)
 // Workspace of the persistent schedule's fix-up: the tiles beyond the last whole round are shared;
 // a tile of nsteps consecutive units cut into runs of at least q units meets at most
 // ceil((nsteps-1)/q) + 1 runs (every run holds one unit when there are fewer units than runs).
+int64_t g_workspace_limit = kFixupMaxBytes;
+
 FixupNeed fixup_need(const Problem &pr, const wpk_conv_config &cfg, int compute_units)
 {
     FixupNeed n = {0, 0, 0, 0};
@@ -189,7 +191,7 @@ FixupNeed fixup_need(const Problem &pr, const wpk_conv_config &cfg, int compute_
     // configurations never find slot data where counters are expected
     n.slots_offset = kFixupCounterBytes;
     n.bytes = n.slots_offset + n.shared_tiles * n.maxc * cfg.bm * cfg.bn * 4;
-    if (n.shared_tiles * 4 > kFixupCounterBytes || n.bytes > kFixupMaxBytes)
+    if (n.shared_tiles * 4 > kFixupCounterBytes || n.bytes > g_workspace_limit)
         n = FixupNeed{0, 0, 0, 0};  // use atomics
     return n;
 }
@@ -524,6 +526,13 @@ int wpk_cache_load(const char *path)
 }
 
 // ---- tuning options and the engine ---------------------------------------------------------------
+int wpk_set_workspace_limit(int64_t bytes)
+{
+    if (bytes < 0) return WPK_E_BAD_ARG;
+    g_workspace_limit = bytes;
+    return WPK_OK;
+}
+
 void wpk_tune_default_options(wpk_tune_options *o)
 {
     if (!o) return;

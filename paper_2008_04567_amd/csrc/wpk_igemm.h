@@ -392,6 +392,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
         }
     }
     const bool atomic = mode == kAtomic;
+    const bool fused = a.bias || a.res || a.relu;  // the host applies these itself after atomics
 
     // ---- epilogue: D[row = channel][col = pixel]; register e of lane l holds row
     //      8*(e/4) + 4*(l/32) + e%4 and column l%32 of its 32x32 block ---------------------------
@@ -408,10 +409,17 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                     int kout = n0 + wave_n * TN + i * 32 + 8 * (e / 4) + 4 * lrow + (e & 3);
                     if (kout < a.K) {
                         float *dst = yp + (size_t)kout * a.PQ;
-                        if (atomic)
+                        if (atomic) {
                             unsafeAtomicAdd(dst, acc[i * NMT + j][e]);
-                        else
-                            *dst = acc[i * NMT + j][e];
+                        } else {
+                            float v = acc[i * NMT + j][e];
+                            if (fused) {
+                                if (a.bias) v += a.bias[kout];
+                                if (a.res) v += a.res[dst - a.y];
+                                if (a.relu) v = fmaxf(v, 0.0f);
+                            }
+                            *dst = v;
+                        }
                     }
                 });
             });

@@ -89,10 +89,23 @@ struct IgemmArgs {
     float *ws;          // [shared tiles][ws_maxc slots][BM*BN] partial tiles
     int32_t *ws_cnt;    // [shared tiles] arrival counters, zero between launches
     int32_t ws_maxc;    // slots per shared tile
+    // fused epilogue, applied where y is stored plainly: y = act(acc + bias[k] + res[n][k][p][q])
+    const float *bias;  // [K] or NULL
+    const float *res;   // laid out like y, or NULL
+    int32_t relu;       // act = max(., 0) when nonzero
+};
+
+// What follows the convolution inside the same launch (Section 2.1, operator fusion).
+struct Epilogue {
+    const float *bias = nullptr;
+    const float *res = nullptr;
+    int relu = 0;
+    bool any() const { return bias || res || relu; }
 };
 
 static const int64_t kFixupCounterBytes = 1 << 20;   // room for 262144 shared tiles
-static const int64_t kFixupMaxBytes = (int64_t)1 << 30;  // beyond this, fall back to atomics
+static const int64_t kFixupMaxBytes = (int64_t)1 << 30;  // default cap; beyond it, atomics
+extern int64_t g_workspace_limit;  // wpk_set_workspace_limit(); set before launches are prepared
 // Fix-up workspace a launch of `cfg` needs (split reduction or persistent): shared tiles, slots per tile, bytes
 // (a fixed-size counter region first, then the slots).  All zero when nothing is shared or the
 // workspace would be too large (the launch then accumulates with atomics).

@@ -64,6 +64,24 @@ def run_gpu(layer, x, w, cfg=None, mode="fwd"):
     return host[guard:guard + n_out].reshape(layer["n"], layer["k"], P, Q)
 
 
+def run_gpu_fused(layer, x, w, bias=None, residual=None, relu=False, cfg=None):
+    """The fused operator through the C ABI; returns the output as a NumPy array."""
+    torch, dev = torch_dev()
+    desc = B.make_desc(layer)
+    P, Q = B.conv_out_shape(desc)
+    n_out = layer["n"] * layer["k"] * P * Q
+    guard = 256
+    buf = torch.full((n_out + 2 * guard,), 12345.0, device=dev, dtype=torch.float32)
+    yd = buf[guard:guard + n_out]
+    B.conv2d_fwd_fused(desc, to_dev(x), to_dev(w), yd, bias=None if bias is None else to_dev(bias),
+                       residual=None if residual is None else to_dev(residual), relu=relu, cfg=cfg)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    assert np.all(host[:guard] == 12345.0) and np.all(host[guard + n_out:] == 12345.0), \
+        "write outside the output tensor"
+    return host[guard:guard + n_out].reshape(layer["n"], layer["k"], P, Q)
+
+
 def check_layer(layer, cfg=None, mode="fwd", what=None):
     x, w = W.make_inputs(layer)
     y_ref, d_ref = oracle_full(layer, x, w)

@@ -237,3 +237,9 @@ def test_engine_random_mode_and_bad_arguments():
         B.ga_search([0, 3], [1, 2], None, fit_sep)       # empty gene range
     with pytest.raises(B.WpkError):
         B.ga_search([0], [3], lambda ch: False, lambda ch: 1.0)   # nothing is legal
+
+
+def test_workspace_limit_argument_check():
+    L = B.lib()
+    assert L.wpk_set_workspace_limit(-1) == B.E_BAD_ARG
+    assert L.wpk_set_workspace_limit(1 << 30) == 0

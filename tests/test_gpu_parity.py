@@ -5,6 +5,8 @@ import ctypes
 import numpy as np
 import pytest
 
+from oracle import conv as oc
+
 from paper_2008_04567_amd import binding as B
 from paper_2008_04567_amd import workloads as W
 from tests import parity as PT
@@ -135,6 +137,87 @@ def test_section3_workloads(layer):
         if B.config_legal(desc, c):
             print(layer["name"], c, flush=True)
             PT.assert_close(PT.run_gpu(layer, x, w, cfg=c), y_ref, d_ref, layer["name"] + repr(c))
+
+
+def _fused_operands(l, seed):
+    rng = np.random.default_rng(seed)
+    P, Q = B.conv_out_shape(B.make_desc(l))
+    bias = rng.uniform(-1, 1, l["k"]).astype(np.float32)
+    res = rng.uniform(-2, 2, (l["n"], l["k"], P, Q)).astype(np.float32)
+    return bias, res
+
+
+def test_fused_epilogue_every_schedule():
+    """Bias, residual and rectifier applied inside the launch: plain tiles, split reduction and
+    persistent schedules (both meet through the workspace), in every combination of the three
+    terms; then the default entry point and the direct kernel's two-launch form."""
+    import itertools
+    l = RAGGED
+    desc = B.make_desc(l)
+    x, w = W.make_inputs(l)
+    bias, res = _fused_operands(l, 5)
+    sh = oc.shape_from_layer(l)
+    cfgs = [B.make_config(64, 32, 16, 2, 1), B.make_config(128, 64, 16, 2, 2, 5),
+            B.make_config(64, 64, 8, 2, 1, persist=2), B.make_config(128, 128, 32, 2, 2, persist=1)]
+    for use_b, use_r, relu in itertools.product((False, True), repeat=3):
+        b_, r_ = (bias if use_b else None), (res if use_r else None)
+        y_ref, d_ref = oc.conv2d_fused(sh, x, w, bias=b_, residual=r_, relu=relu)
+        for c in cfgs + [None]:
+            assert c is None or B.config_legal(desc, c)
+            what = "bias %d residual %d relu %d %r" % (use_b, use_r, relu, c)
+            print(what, flush=True)
+            y = PT.run_gpu_fused(l, x, w, bias=b_, residual=r_, relu=relu, cfg=c)
+            PT.assert_close(y, y_ref, d_ref, what)
+    big = W.layer("big_filter", 1, 2, (20, 20), 3, (17, 2), 1, 2, 1, x_dist="u11", w_dist="u11", seed=5)
+    x, w = W.make_inputs(big)
+    bias, res = _fused_operands(big, 6)
+    y_ref, d_ref = oc.conv2d_fused(oc.shape_from_layer(big), x, w, bias=bias, residual=res, relu=True)
+    PT.assert_close(PT.run_gpu_fused(big, x, w, bias=bias, residual=res, relu=True), y_ref, d_ref,
+                    "direct kernel + epilogue")
+
+
+def test_without_workspace_shared_tiles_use_atomics():
+    """With the workspace turned off, split and persistent launches zero y and accumulate with
+    fp32 atomics, and a fused epilogue follows as a launch of its own."""
+    l = RAGGED
+    desc = B.make_desc(l)
+    x, w = W.make_inputs(l)
+    bias, res = _fused_operands(l, 15)
+    sh = oc.shape_from_layer(l)
+    y_ref, d_ref = PT.oracle_full(l, x, w)
+    f_ref, fd_ref = oc.conv2d_fused(sh, x, w, bias=bias, residual=res, relu=True)
+    B.set_workspace_limit(0)
+    try:
+        for c in [B.make_config(128, 64, 16, 2, 2, 5), B.make_config(64, 64, 8, 2, 1, 11, 0),
+                  B.make_config(64, 64, 8, 2, 1, persist=2), B.make_config(64, 32, 16, 2, 1, persist=4)]:
+            assert B.config_legal(desc, c)
+            print(c, flush=True)
+            PT.assert_close(PT.run_gpu(l, x, w, cfg=c), y_ref, d_ref, repr(c) + " atomics")
+            PT.assert_close(PT.run_gpu_fused(l, x, w, bias=bias, residual=res, relu=True, cfg=c),
+                            f_ref, fd_ref, repr(c) + " atomics, fused")
+    finally:
+        B.set_workspace_limit(1 << 30)
+
+
+def test_fused_epilogue_rectifier_bites_and_full_size():
+    """A config-3 layer at full size with all three terms, sampled against the oracle; the bias is
+    chosen so that about half of the outputs are cut off by the rectifier."""
+    l = W.config3()[2]
+    desc = B.make_desc(l)
+    x, w = W.make_inputs(l)
+    bias, res = _fused_operands(l, 9)
+    bias -= 1.0
+    c = B.make_config(64, 64, 16, 2, 2, 5)
+    y = PT.run_gpu_fused(l, x, w, bias=bias, residual=res, relu=True, cfg=c)
+    frac = float((y == 0).mean())
+    assert 0.1 < frac < 0.9, frac
+    rng = np.random.default_rng(3)
+    idx = np.unique(rng.integers(0, y.size, 4096))
+    yc, dc = oc.conv2d_sampled(oc.shape_from_layer(l), x, w, idx)
+    kk = (idx // (y.shape[2] * y.shape[3])) % l["k"]
+    z = yc + bias.astype(np.float64)[kk] + res.reshape(-1).astype(np.float64)[idx]
+    d = dc + np.abs(bias.astype(np.float64))[kk] + np.abs(res.reshape(-1).astype(np.float64))[idx]
+    PT.assert_close(y.reshape(-1)[idx], np.maximum(z, 0.0), d, "config 3 layer fused")
 
 
 def test_oversized_filter_uses_the_direct_kernel():

@@ -79,3 +79,51 @@ def test_tuner_small_budget_result_is_legal_cached_and_correct():
     assert B.conv_tune(desc) == cid                      # cache hit returns at once
     PT.check_layer(l)                                    # one-shot path now runs the tuned config
     B.cache_clear()
+
+
+def test_plan_fused_basic_block():
+    """Two chained 3x3 layers of a residual block through a plan with fused epilogues:
+    y1 = relu(conv(x, w1) + b1); y2 = relu(conv(y1, w2) + b2 + x).  The second layer is checked
+    with the GPU's own y1 as the oracle's input, so each layer is held to the per-layer bound."""
+    from oracle import conv as oc
+    torch, dev = PT.torch_dev()
+    la = W.layer("blk.c1", 2, 24, (17, 13), 24, 3, 1, 1, x_dist="u11", seed=91)
+    lb = W.layer("blk.c2", 2, 24, (17, 13), 24, 3, 1, 1, x_dist="u11", seed=92)
+    descs = [B.make_desc(la), B.make_desc(lb)]
+    plan = B.Plan(descs, tune=False)
+    assert plan.num_unique() == 1
+    plan.set_layer_config(1, B.make_config(64, 32, 8, 2, 1, 3))     # split reduction, workspace
+    x, w1 = W.make_inputs(la)
+    _, w2 = W.make_inputs(lb)
+    rng = np.random.default_rng(4)
+    b1 = rng.uniform(-0.5, 0.5, 24).astype(np.float32)
+    b2 = rng.uniform(-0.5, 0.5, 24).astype(np.float32)
+    xd = PT.to_dev(x)
+    y1 = torch.empty((2, 24, 17, 13), device=dev)
+    y2 = torch.empty_like(y1)
+    plan.set_weights(0, PT.to_dev(w1))
+    plan.set_weights(1, PT.to_dev(w2))
+    plan.set_epilogue(0, PT.to_dev(b1), relu=True)
+    plan.set_epilogue(1, PT.to_dev(b2), relu=True)
+    xa, ya = plan.pointer_arrays([xd, y1], [y1, y2])
+    ra = plan.residual_array([None, xd])
+    for _ in range(2):
+        plan.run_fused(xa, ra, ya)
+    torch.cuda.synchronize()
+    y1h, y2h = y1.cpu().numpy(), y2.cpu().numpy()
+    r1, d1 = oc.conv2d_fused(oc.shape_from_layer(la), x, w1, bias=b1, relu=True)
+    PT.assert_close(y1h, r1, d1, "block layer 1")
+    r2, d2 = oc.conv2d_fused(oc.shape_from_layer(lb), y1h, w2, bias=b2, residual=x, relu=True)
+    PT.assert_close(y2h, r2, d2, "block layer 2")
+    # the plain run entry points apply the layer's epilogue too (no residual)
+    plan.run_layer(1, y1, y2)
+    torch.cuda.synchronize()
+    r2n, d2n = oc.conv2d_fused(oc.shape_from_layer(lb), y1h, w2, bias=b2, relu=True)
+    PT.assert_close(y2.cpu().numpy(), r2n, d2n, "block layer 2 without residual")
+    # and the epilogue can be taken away again
+    plan.set_epilogue(1, None, relu=False)
+    plan.run_layer(1, y1, y2)
+    torch.cuda.synchronize()
+    r2p, d2p, _ = oc.conv2d(oc.shape_from_layer(lb), y1h, w2)
+    PT.assert_close(y2.cpu().numpy(), r2p, d2p, "block layer 2 plain")
+    plan.destroy()
