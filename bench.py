@@ -17,6 +17,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 FP32_MFMA_PEAK_TFLOPS = 157.3   # 256 CUs x 256 FLOP/clk x 2.4 GHz
+HBM_PEAK_GBS = 8000.0           # HBM3E, published
 HBM_PEAK_GBS = 8000.0
 
 
@@ -76,6 +77,12 @@ def main():
     ap.add_argument("--tune-mode", type=int, default=0, help="0 genetic, 1 random, 2 exhaustive")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--verbose-tune", action="store_true")
+    ap.add_argument("--cold", action="store_true",
+                    help="rotate x and y through a pool larger than the 256 MB memory-side cache, so "
+                         "that every pass reads its activations from HBM (weights stay resident)")
+    ap.add_argument("--fused", nargs="?", const="bias,residual,relu", default="",
+                    help="give every layer a fused epilogue: any of bias,residual,relu (all three "
+                         "when given without a value)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device copy (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -117,28 +124,52 @@ def main():
             B.cache_save(args.cache)
     t_tune = time.perf_counter() - t_tune
 
+    epi = set(t for t in args.fused.split(",") if t)
+    assert epi <= {"bias", "residual", "relu"}, "--fused takes bias,residual,relu"
+    use_res = "residual" in epi
     plan = B.Plan(descs, tune=False)
-    xs, ys, flops = [], [], []
+    flops, act_bytes = [], 0
+    for l, d in zip(layers, descs):
+        P, Q = B.conv_out_shape(d)
+        flops.append(B.conv_flops(d))
+        act_bytes += 4 * (l["n"] * l["c"] * l["h"] * l["w"] + l["n"] * l["k"] * P * Q * (2 if use_res else 1))
+    # cold runs rotate through `copies` sets of activations, together above 600 MB (at most 16 GB)
+    copies = 1
+    if args.cold:
+        copies = max(2, min(-(-600 * 2 ** 20 // act_bytes) + 1, (16 * 2 ** 30) // act_bytes))
+    xs, ys, rs = [[] for _ in range(copies)], [[] for _ in range(copies)], [[] for _ in range(copies)]
     for i, (l, d) in enumerate(zip(layers, descs)):
         x, w = W.make_inputs(l)
         P, Q = B.conv_out_shape(d)
-        xs.append(torch.from_numpy(x).to(dev))
-        wd = torch.from_numpy(w).to(dev)
-        ys.append(torch.empty((l["n"], l["k"], P, Q), device=dev, dtype=torch.float32))
-        plan.set_weights(i, wd)
-        flops.append(B.conv_flops(d))
-    xa, ya = plan.pointer_arrays(xs, ys)
+        xh = torch.from_numpy(x)
+        for c in range(copies):
+            xs[c].append(xh.to(dev))
+            ys[c].append(torch.empty((l["n"], l["k"], P, Q), device=dev, dtype=torch.float32))
+            rs[c].append(torch.rand((l["n"], l["k"], P, Q), device=dev, dtype=torch.float32)
+                         if use_res else None)
+        plan.set_weights(i, torch.from_numpy(w).to(dev))
+        if epi:
+            plan.set_epilogue(i, torch.zeros(l["k"], device=dev, dtype=torch.float32)
+                              if "bias" in epi else None, relu="relu" in epi)
+    arrays = [plan.pointer_arrays(xs[c], ys[c]) + (plan.residual_array(rs[c]),) for c in range(copies)]
     stream = torch.cuda.current_stream()
     torch.cuda.synchronize()
 
-    for _ in range(args.warmup):
-        plan.run(xa, ya, stream)
+    def one_pass(step):
+        xa, ya, ra = arrays[step % copies]
+        if use_res:
+            plan.run_fused(xa, ra, ya, stream)
+        else:
+            plan.run(xa, ya, stream)
+
+    for s_ in range(args.warmup):
+        one_pass(s_)
     torch.cuda.synchronize()
 
     # ---- timed region: exactly `steps` passes, bracketed by synchronisation -----------------
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        plan.run(xa, ya, stream)
+    for s_ in range(args.steps):
+        one_pass(s_)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
@@ -150,8 +181,9 @@ def main():
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(n + 1)] for _ in range(args.steps)]
     for s in range(args.steps):
         ev[s][0].record(stream)
+        c = s % copies
         for i in range(n):
-            plan.run_layer(i, xs[i], ys[i], stream)
+            plan.run_layer_fused(i, xs[c][i], rs[c][i], ys[c][i], stream)
             ev[s][i + 1].record(stream)
     torch.cuda.synchronize()
     per_layer_us = [1e3 * float(np.mean([ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(args.steps)]))
@@ -163,28 +195,41 @@ def main():
         d = descs[i]
         P, Q = B.conv_out_shape(d)
         abytes = 4.0 * (l["n"] * l["c"] * l["h"] * l["w"] + l["k"] * l["c"] * l["r"] * l["s"]
-                        + l["n"] * l["k"] * P * Q)
+                        + l["n"] * l["k"] * P * Q * (2 if use_res else 1) + (l["k"] if "bias" in epi else 0))
+        gbs = abytes / (per_layer_us[i] * 1e-6) / 1e9
+        # which roofline bounds the layer: the longer of flops at MFMA peak and bytes at HBM peak
+        bound = "mfma" if flops[i] / (FP32_MFMA_PEAK_TFLOPS * 1e12) >= abytes / (HBM_PEAK_GBS * 1e9) else "hbm"
         rows.append({"layer": l["name"], "kernel": B.config_kernel_name(cfg), "split_k": cfg.split_k,
                      "xcd_remap": cfg.xcd_remap, "persist": cfg.persist, "stages": cfg.stages,
                      "us": round(per_layer_us[i], 2),
                      "tflops": round(tf, 2), "pct_fp32_mfma_peak": round(100 * tf / FP32_MFMA_PEAK_TFLOPS, 1),
-                     "gbs_algorithmic": round(abytes / (per_layer_us[i] * 1e-6) / 1e9, 1)})
-        log("%-28s %-30s split %2d persist %d  %9.2f us  %7.2f TFLOP/s  %5.1f%% of fp32 MFMA peak  %7.1f GB/s"
+                     "gbs_algorithmic": round(gbs, 1), "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1),
+                     "bound": bound, "flops": flops[i], "bytes_algorithmic": abytes})
+        log("%-28s %-30s split %2d persist %d  %9.2f us  %7.2f TFLOP/s  %5.1f%% of fp32 MFMA peak  "
+            "%7.1f GB/s  %4.1f%% of HBM peak  (%s-bound)"
             % (l["name"], rows[-1]["kernel"], cfg.split_k, cfg.persist, per_layer_us[i], tf,
-               rows[-1]["pct_fp32_mfma_peak"], rows[-1]["gbs_algorithmic"]))
+               rows[-1]["pct_fp32_mfma_peak"], gbs, rows[-1]["pct_hbm_peak"], bound))
     dom = int(np.argmax(per_layer_us))
-    dom_tf = flops[dom] / (per_layer_us[dom] * 1e-6) / 1e12
-    roofline = {"bound": "mfma", "achieved": round(dom_tf, 3), "peak": FP32_MFMA_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(dom_tf / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
-                "kernel": rows[dom]["kernel"], "layer": rows[dom]["layer"],
-                "flops_per_launch": flops[dom], "avg_us": round(per_layer_us[dom], 2)}
+    if rows[dom]["bound"] == "mfma":
+        roofline = {"bound": "mfma", "achieved": rows[dom]["tflops"], "peak": FP32_MFMA_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(rows[dom]["tflops"] / FP32_MFMA_PEAK_TFLOPS, 4),
+                    "traffic": None, "flops_per_launch": flops[dom]}
+    else:
+        roofline = {"bound": "hbm", "achieved": rows[dom]["gbs_algorithmic"], "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(rows[dom]["gbs_algorithmic"] / HBM_PEAK_GBS, 4),
+                    "traffic": None, "bytes_per_launch": rows[dom]["bytes_algorithmic"]}
+    roofline.update({"kernel": rows[dom]["kernel"], "layer": rows[dom]["layer"],
+                     "avg_us": round(per_layer_us[dom], 2)})
 
     out = {"metric": "conv2d fwd TFLOP/s (fp32, direct-convolution FLOP count) over the layer set",
            "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": wl_text, "layers": n, "tuned": not args.no_tune,
-                      "tune_seconds": round(t_tune, 1)},
+                      "tune_seconds": round(t_tune, 1),
+                      "activations": "rotated through %d copies (read from HBM)" % copies if args.cold
+                                     else "one set, resident in the memory-side cache between passes",
+                      "epilogue": "fused: " + "+".join(sorted(epi)) if epi else "none"},
            "pct_fp32_mfma_peak": round(100 * value / FP32_MFMA_PEAK_TFLOPS, 2),
            "roofline": roofline, "layers": rows}
     if args.calibrate_copy:

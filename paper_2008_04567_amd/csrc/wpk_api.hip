@@ -332,6 +332,7 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     a.x_bytes = (uint32_t)(pr.x_elems * 4);
     a.x_bias = (uint32_t)((d.pad_h * d.w + d.pad_w) * 4);
     a.w_bytes = (uint32_t)((int64_t)pr.CRSpad * pr.Kpad * 4);
+    a.y_bytes = (uint32_t)(pr.y_elems * 4);
     a.persist = cfg.persist;
     a.grid_persist = cfg.persist * (g_cus > 0 ? g_cus : 256);
     a.ws = nullptr;

@@ -392,36 +392,73 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
         }
     }
     const bool atomic = mode == kAtomic;
-    const bool fused = a.bias || a.res || a.relu;  // the host applies these itself after atomics
+    // the host applies the epilogue itself after a launch that accumulates with atomics
+    const bool fused = !atomic && (a.bias || a.res || a.relu);
 
     // ---- epilogue: D[row = channel][col = pixel]; register e of lane l holds row
-    //      8*(e/4) + 4*(l/32) + e%4 and column l%32 of its 32x32 block ---------------------------
+    //      8*(e/4) + 4*(l/32) + e%4 and column l%32 of its 32x32 block.  Buffer addressing: one
+    //      32-bit lane offset per block plus a wave-uniform offset per register, instead of a
+    //      64-bit address per output.  A NULL bias or residual becomes a buffer of zero records,
+    //      whose loads return 0. ------------------------------------------------------------------
+    const __amdgpu_buffer_rsrc_t yrsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.y, 0, (int)a.y_bytes, 0x00020000);
+    const int PQ4 = a.PQ * 4;
     static_for<NMT>([&](auto J) WPK_LAMBDA {
         constexpr int j = decltype(J)::value;
         int m = m0 + wave_m * TM + j * 32 + lcol;
         if (m < a.M) {
             int n = m / a.PQ, pq = m - n * a.PQ;
-            float *yp = a.y + (size_t)n * a.K * a.PQ + pq;
             static_for<NNT>([&](auto I) WPK_LAMBDA {
                 constexpr int i = decltype(I)::value;
-                static_for<16>([&](auto E) WPK_LAMBDA {
-                    constexpr int e = decltype(E)::value;
-                    int kout = n0 + wave_n * TN + i * 32 + 8 * (e / 4) + 4 * lrow + (e & 3);
-                    if (kout < a.K) {
-                        float *dst = yp + (size_t)kout * a.PQ;
-                        if (atomic) {
-                            unsafeAtomicAdd(dst, acc[i * NMT + j][e]);
-                        } else {
-                            float v = acc[i * NMT + j][e];
-                            if (fused) {
-                                if (a.bias) v += a.bias[kout];
-                                if (a.res) v += a.res[dst - a.y];
-                                if (a.relu) v = fmaxf(v, 0.0f);
-                            }
-                            *dst = v;
+                const int kbase = n0 + wave_n * TN + i * 32 + 4 * lrow;  // + 8*(e/4) + e%4
+                // byte offset of (n, kbase, pq) in y; only used for channels below K, where it
+                // is below y_bytes < 2^32
+                const unsigned voff = (unsigned)((((size_t)n * a.K + kbase) * a.PQ + pq) * 4);
+                if (fused) {
+                    const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
+                        (void *)(a.bias ? a.bias : a.y), 0, a.bias ? a.K * 4 : 0, 0x00020000);
+                    const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
+                        (void *)(a.res ? a.res : a.y), 0, a.res ? (int)a.y_bytes : 0, 0x00020000);
+                    // everything the 16 outputs of this block add is fetched first, so the loads
+                    // are all in flight together; then the stores
+                    float add[16];
+                    static_for<16>([&](auto E) WPK_LAMBDA {
+                        constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
+                        float t = __builtin_bit_cast(
+                            float, __builtin_amdgcn_raw_buffer_load_b32(brsrc, kbase * 4, de * 4, 0));
+                        if (kbase + de < a.K)
+                            t += __builtin_bit_cast(
+                                float, __builtin_amdgcn_raw_buffer_load_b32(rrsrc, voff, de * PQ4, 0));
+                        add[e] = t;
+                    });
+                    static_for<16>([&](auto E) WPK_LAMBDA {
+                        constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
+                        if (kbase + de < a.K) {
+                            float v = acc[i * NMT + j][e] + add[e];
+                            v = a.relu ? fmaxf(v, 0.0f) : v;
+                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
+                                                                  voff, de * PQ4, 0);
                         }
-                    }
-                });
+                    });
+                } else if (atomic) {
+                    float *yp = a.y + (size_t)n * a.K * a.PQ + pq;
+                    static_for<16>([&](auto E) WPK_LAMBDA {
+                        constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
+                        if (kbase + de < a.K)
+                            unsafeAtomicAdd(yp + (size_t)(kbase + de) * a.PQ, acc[i * NMT + j][e]);
+                    });
+                } else {
+                    static_for<16>([&](auto E) WPK_LAMBDA {
+                        constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
+                        if (kbase + de < a.K) {
+                            // a copy first: a bit cast taken straight from a vector element
+                            // reads element 0 with this compiler
+                            const float v = acc[i * NMT + j][e];
+                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
+                                                                  voff, de * PQ4, 0);
+                        }
+                    });
+                }
             });
         }
     });

@@ -85,6 +85,7 @@ struct IgemmArgs {
     uint32_t x_bytes;   // size of x
     uint32_t x_bias;    // (pad_h*W + pad_w)*4: added to every tap offset, subtracted from the base
     uint32_t w_bytes;   // size of the packed weights
+    uint32_t y_bytes;   // size of y (and of a residual)
     // fix-up workspace of shared tiles (NULL = accumulate with atomics into zeroed y instead)
     float *ws;          // [shared tiles][ws_maxc slots][BM*BN] partial tiles
     int32_t *ws_cnt;    // [shared tiles] arrival counters, zero between launches
