@@ -83,6 +83,9 @@ def main():
     ap.add_argument("--fused", nargs="?", const="bias,residual,relu", default="",
                     help="give every layer a fused epilogue: any of bias,residual,relu (all three "
                          "when given without a value)")
+    ap.add_argument("--workspace-limit", type=int, default=None,
+                    help="bytes; wpk_set_workspace_limit before tuning (0: atomics instead of a workspace)")
+    ap.add_argument("--refine", type=int, default=None, help="refinement rounds of the tuner")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device copy (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -101,11 +104,15 @@ def main():
     descs = [B.make_desc(l) for l in layers]
     log("device %s, %d CUs; workload %s" % (dev_name, cus, wl_text))
 
+    if args.workspace_limit is not None:
+        B.set_workspace_limit(args.workspace_limit)
     if args.cache and os.path.exists(args.cache):
         log("loaded %d cached search results" % B.cache_load(args.cache))
     t_tune = time.perf_counter()
     if not args.no_tune:
         opt = B.tune_default_options(mode=args.tune_mode, verbose=1 if args.verbose_tune else 0)
+        if args.refine is not None:
+            opt.refine = args.refine
         seen = set()
         for l, d in zip(layers, descs):
             key = W.shape_key(l)
@@ -115,9 +122,10 @@ def main():
             hit = B.cache_lookup(d) is not None
             cid, rep = B.conv_tune_ex(d, opt, force=False)
             if not hit:
-                log("tuned %-28s %-30s split %2d remap %d persist %d: %8.2f us (default %8.2f us), "
+                log("tuned %-28s %-30s split %2d remap %d persist %d reduce %d: %8.2f us (default %8.2f us), "
                     "%d evals, %d gens, %.1f s" % (l["name"], B.config_kernel_name(rep.best),
                                          rep.best.split_k, rep.best.xcd_remap, rep.best.persist,
+                                         rep.best.reduce,
                                          rep.best_us, rep.default_us,
                                          rep.evaluations, rep.generations, rep.seconds))
         if args.cache:
@@ -201,6 +209,7 @@ def main():
         bound = "mfma" if flops[i] / (FP32_MFMA_PEAK_TFLOPS * 1e12) >= abytes / (HBM_PEAK_GBS * 1e9) else "hbm"
         rows.append({"layer": l["name"], "kernel": B.config_kernel_name(cfg), "split_k": cfg.split_k,
                      "xcd_remap": cfg.xcd_remap, "persist": cfg.persist, "stages": cfg.stages,
+                     "reduce": "atomics" if cfg.reduce else "workspace",
                      "us": round(per_layer_us[i], 2),
                      "tflops": round(tf, 2), "pct_fp32_mfma_peak": round(100 * tf / FP32_MFMA_PEAK_TFLOPS, 1),
                      "gbs_algorithmic": round(gbs, 1), "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1),

@@ -82,7 +82,7 @@ int wpk_last_hip_error(void);
  * split_k may not exceed the number of reduction steps, and the persistent schedule excludes
  * split_k > 1 and xcd_remap.
  */
-#define WPK_N_GENES 9
+#define WPK_N_GENES 10
 typedef struct wpk_conv_config {
     int32_t bm;        /* output pixels per workgroup tile:      64, 128, 256                        */
     int32_t bn;        /* output channels per workgroup tile:    32, 64, 128                        */
@@ -95,6 +95,11 @@ typedef struct wpk_conv_config {
                        /* workgroups per compute unit, the reduction steps of the tiles that do   */
                        /* not fill a whole round dealt out evenly among them (split_k must be 1)   */
     int32_t stages;    /* input tiles in flight in registers between global memory and LDS: 1..3   */
+    int32_t reduce;    /* how workgroups that share a tile (split_k > 1 or persist > 0) add up:      */
+                       /* 0: partial tiles through a device workspace, the last to arrive sums and */
+                       /*    stores (no zeroing of y, fused epilogue applied in the same launch);   */
+                       /* 1: fp32 atomics into y zeroed by a launch of its own (cheaper when many   */
+                       /*    small slices meet).  Must be 0 when nothing is shared                  */
 } wpk_conv_config;
 
 /* Gene ranges as index ranges into the value lists above: lo[g] = 0, hi[g] = count-1.
@@ -149,8 +154,8 @@ int wpk_conv2d_ref(const wpk_conv_desc *d, const float *x, const float *w, float
 
 /* ---- tuning (Section 2.3 "Genetic search", Steps 1-4; cache: Section 3.3) --------------------- */
 typedef struct wpk_tune_options {
-    int32_t population;   /* |a|, default 48                                                     */
-    int32_t elites;       /* k, default 6                                                        */
+    int32_t population;   /* |a|, default 64                                                     */
+    int32_t elites;       /* k, default 8                                                        */
     int32_t next_population; /* |a'|, default = population                                        */
     int32_t participants; /* m, default = population                                              */
     int32_t max_generations; /* default 16                                                       */

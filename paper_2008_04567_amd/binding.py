@@ -10,14 +10,14 @@ import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libwpk.so")
-N_GENES = 9
+N_GENES = 10
 
 OK, E_BAD_DESC, E_NULL_PTR, E_UNSUPPORTED, E_HIP, E_NO_CONFIG, E_BAD_ARG, E_IO, E_VERIFY = (
     0, -1, -2, -3, -4, -5, -6, -7, -8)
 
 DESC_FIELDS = ("n", "c", "h", "w", "k", "r", "s", "stride_h", "stride_w", "pad_h", "pad_w",
                "dil_h", "dil_w", "dtype", "layout")
-CONFIG_FIELDS = ("bm", "bn", "bk", "wm", "wn", "split_k", "xcd_remap", "persist", "stages")
+CONFIG_FIELDS = ("bm", "bn", "bk", "wm", "wn", "split_k", "xcd_remap", "persist", "stages", "reduce")
 
 
 class ConvDesc(ctypes.Structure):
@@ -156,8 +156,8 @@ def make_desc(layer=None, **kw):
     return d
 
 
-def make_config(bm, bn, bk, wm, wn, split_k=1, xcd_remap=1, persist=0, stages=2):
-    return ConvConfig(bm, bn, bk, wm, wn, split_k, 0 if persist else xcd_remap, persist, stages)
+def make_config(bm, bn, bk, wm, wn, split_k=1, xcd_remap=1, persist=0, stages=2, reduce=0):
+    return ConvConfig(bm, bn, bk, wm, wn, split_k, 0 if persist else xcd_remap, persist, stages, reduce)
 
 
 def _ptr(t):
@@ -246,7 +246,7 @@ def config_kernel_name(cfg):
     return lib().wpk_config_kernel_name(ctypes.byref(cfg)).decode()
 
 
-def legal_configs(desc, split_k=None, xcd_remap=None, persist=None, stages=None):
+def legal_configs(desc, split_k=None, xcd_remap=None, persist=None, stages=None, reduce=None):
     """Every legal configuration of a descriptor (enumeration of the gene space)."""
     import itertools
     lo, hi = config_gene_ranges()
@@ -260,6 +260,8 @@ def legal_configs(desc, split_k=None, xcd_remap=None, persist=None, stages=None)
         if persist is not None and c.persist not in persist:
             continue
         if stages is not None and c.stages not in stages:
+            continue
+        if reduce is not None and c.reduce not in reduce:
             continue
         if config_legal(desc, c):
             out.append(c)

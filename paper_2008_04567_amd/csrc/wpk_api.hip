@@ -543,8 +543,8 @@ static double tune_fitness(const int32_t *genes, int32_t n, void *user)
     }
     t->times_us[wpk_config_id(&cfg)] = us;
     if (t->opt.verbose >= 2)
-        fprintf(stderr, "[wpk tune] %-32s split %2d remap %d persist %d: %9.2f us\n",
-                wpk_config_kernel_name(&cfg), cfg.split_k, cfg.xcd_remap, cfg.persist, us);
+        fprintf(stderr, "[wpk tune] %-32s split %2d remap %d persist %d reduce %d: %9.2f us\n",
+                wpk_config_kernel_name(&cfg), cfg.split_k, cfg.xcd_remap, cfg.persist, cfg.reduce, us);
     return 1.0 / us;
 }
 

@@ -24,7 +24,8 @@ const int32_t kSplitVals[18] = {1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 1
 const int32_t kRemapVals[2] = {0, 1};
 const int32_t kPersistVals[5] = {0, 1, 2, 3, 4};
 const int32_t kStageVals[3] = {1, 2, 3};
-const int kGeneCounts[WPK_N_GENES] = {3, 3, 3, 3, 3, 18, 2, 5, 3};
+const int32_t kReduceVals[2] = {0, 1};
+const int kGeneCounts[WPK_N_GENES] = {3, 3, 3, 3, 3, 18, 2, 5, 3, 2};
 
 const int32_t *gene_values(int g)
 {
@@ -38,6 +39,7 @@ const int32_t *gene_values(int g)
     case 6: return kRemapVals;
     case 7: return kPersistVals;
     case 8: return kStageVals;
+    case 9: return kReduceVals;
     }
     return nullptr;
 }
@@ -134,6 +136,7 @@ static const int32_t *cfg_fields(const wpk_conv_config *c, int32_t f[WPK_N_GENES
     f[6] = c->xcd_remap;
     f[7] = c->persist;
     f[8] = c->stages;
+    f[9] = c->reduce;
     return f;
 }
 
@@ -154,6 +157,8 @@ bool legal_for(const Problem &pr, const wpk_conv_config &cfg)
     if (cfg.split_k > nsteps) return false;
     // the persistent schedule balances the reduction itself: no fixed slices, no tile remap
     if (cfg.persist > 0 && (cfg.split_k != 1 || cfg.xcd_remap != 0)) return false;
+    // how partial tiles meet is a choice only where tiles can be shared
+    if (cfg.reduce != 0 && cfg.split_k == 1 && cfg.persist == 0) return false;
     int64_t tiles = ((pr.M + cfg.bm - 1) / cfg.bm) * ((pr.d.k + cfg.bn - 1) / cfg.bn);
     if (tiles * cfg.split_k > 0x7fffffff) return false;
     return true;
@@ -167,6 +172,7 @@ int64_t g_workspace_limit = kFixupMaxBytes;
 FixupNeed fixup_need(const Problem &pr, const wpk_conv_config &cfg, int compute_units)
 {
     FixupNeed n = {0, 0, 0, 0};
+    if (cfg.reduce != 0) return n;  // atomics asked for
     if (compute_units <= 0) compute_units = 256;
     int64_t tiles = ((pr.M + cfg.bm - 1) / cfg.bm) * ((pr.d.k + cfg.bn - 1) / cfg.bn);
     int64_t nsteps = (pr.CRS + cfg.bk - 1) / cfg.bk;
@@ -204,11 +210,11 @@ void default_config(const Problem &pr, int compute_units, wpk_conv_config *out)
 {
     if (compute_units <= 0) compute_units = 256;
     double best = 1e300;
-    wpk_conv_config bc = {128, 64, 16, 2, 2, 1, 1, 0, 2};
+    wpk_conv_config bc = {128, 64, 16, 2, 2, 1, 1, 0, 2, 0};
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
         for (int si = 0; si < kGeneCounts[5]; ++si) {
-            wpk_conv_config c = {v.bm, v.bn, v.bk, v.wm, v.wn, kSplitVals[si], 1, 0, v.stages};
+            wpk_conv_config c = {v.bm, v.bn, v.bk, v.wm, v.wn, kSplitVals[si], 1, 0, v.stages, 0};
             if (!legal_for(pr, c)) continue;
             double nsteps = ceil((double)pr.CRS / v.bk);
             double steps = ceil(nsteps / c.split_k);
@@ -227,6 +233,10 @@ void default_config(const Problem &pr, int compute_units, wpk_conv_config *out)
             if (cost < best) { best = cost; bc = c; }
         }
     }
+    // many small slices: summing their slots one after another costs the last workgroup more
+    // than atomics and a zeroing launch do
+    int64_t nsteps = (pr.CRS + bc.bk - 1) / bc.bk, per = (nsteps + bc.split_k - 1) / bc.split_k;
+    bc.reduce = (nsteps + per - 1) / per > 8 ? 1 : 0;
     *out = bc;
 }
 
@@ -388,6 +398,7 @@ int wpk_config_from_genes(const int32_t genes[WPK_N_GENES], wpk_conv_config *out
     out->xcd_remap = kRemapVals[genes[6]];
     out->persist = kPersistVals[genes[7]];
     out->stages = kStageVals[genes[8]];
+    out->reduce = kReduceVals[genes[9]];
     return WPK_OK;
 }
 
@@ -489,13 +500,13 @@ int wpk_cache_save(const char *path)
     FILE *f = fopen(path, "w");
     if (!f) return WPK_E_IO;
     std::lock_guard<std::mutex> g(g_cache_mu);
-    fprintf(f, "# wpk search-result cache v2: key bm bn bk wm wn split_k xcd_remap persist stages microseconds\n");
+    fprintf(f, "# wpk search-result cache v3: key bm bn bk wm wn split_k xcd_remap persist stages reduce microseconds\n");
     for (auto &kv : g_cache) {
         std::string key = kv.first;
         std::replace(key.begin(), key.end(), ' ', '_');
         const wpk_conv_config &c = kv.second.cfg;
-        fprintf(f, "%s %d %d %d %d %d %d %d %d %d %.6f\n", key.c_str(), c.bm, c.bn, c.bk, c.wm, c.wn,
-                c.split_k, c.xcd_remap, c.persist, c.stages, kv.second.us);
+        fprintf(f, "%s %d %d %d %d %d %d %d %d %d %d %.6f\n", key.c_str(), c.bm, c.bn, c.bk, c.wm, c.wn,
+                c.split_k, c.xcd_remap, c.persist, c.stages, c.reduce, kv.second.us);
     }
     return fclose(f) == 0 ? WPK_OK : WPK_E_IO;
 }
@@ -513,9 +524,9 @@ int wpk_cache_load(const char *path)
         char key[512];
         wpk_conv_config c;
         double us;
-        if (sscanf(line, "%511s %d %d %d %d %d %d %d %d %d %lf", key, &c.bm, &c.bn, &c.bk, &c.wm, &c.wn,
-                   &c.split_k, &c.xcd_remap, &c.persist, &c.stages, &us) != 11)
-            continue;
+        if (sscanf(line, "%511s %d %d %d %d %d %d %d %d %d %d %lf", key, &c.bm, &c.bn, &c.bk, &c.wm,
+                   &c.wn, &c.split_k, &c.xcd_remap, &c.persist, &c.stages, &c.reduce, &us) != 12)
+            continue;  // also skips lines of older formats: those layers are searched again
         int32_t genes[WPK_N_GENES];
         if (wpk_config_to_genes(&c, genes) != WPK_OK) continue;
         g_cache[key] = CacheEntry{c, us};
@@ -537,10 +548,10 @@ void wpk_tune_default_options(wpk_tune_options *o)
 {
     if (!o) return;
     memset(o, 0, sizeof *o);
-    o->population = 48;
-    o->elites = 6;
-    o->next_population = 48;
-    o->participants = 48;
+    o->population = 64;
+    o->elites = 8;
+    o->next_population = 64;
+    o->participants = 64;
     o->max_generations = 16;
     o->patience = 5;
     o->mutation = 0.15;

@@ -377,18 +377,45 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
         __syncthreads();  // everyone has read `arrival` before a later segment overwrites it
         if (arrived_before != fix_n - 1) return;  // not the last: done with this tile
         if (tid == 0) a.ws_cnt[fix_j] = 0;        // leave the counter clean for the next launch
-        for (int sl = 0; sl < fix_n; ++sl) {
-            if (sl == fix_slot) continue;
-            const int other = (sl * (BM * BN) + 4 * tid) * 4;
-            static_for<NNT * NMT * 4>([&](auto Q) WPK_LAMBDA {
-                constexpr int qd = decltype(Q)::value, ij = qd / 4, e4 = qd % 4;
-                v4f v = __builtin_bit_cast(
-                    v4f, __builtin_amdgcn_raw_buffer_load_b128(srsrc, other, qd * 16 * T, kCoherent));
-                acc[ij][4 * e4] += v[0];
-                acc[ij][4 * e4 + 1] += v[1];
-                acc[ij][4 * e4 + 2] += v[2];
-                acc[ij][4 * e4 + 3] += v[3];
-            });
+        // Add the other workgroups' slots to this one's accumulators.
+        if constexpr (NNT * NMT == 1) {
+            // a single 32x32 block per wave has little to load per slot: two slots at a time (a
+            // slot number past the last becomes an out-of-range offset, which loads 0)
+            for (int t0 = 0; t0 < fix_n - 1; t0 += 2) {
+                v4f part[2][4];
+                static_for<2>([&](auto U) WPK_LAMBDA {
+                    constexpr int u = decltype(U)::value;
+                    const int t = t0 + u, sl = t + (t >= fix_slot ? 1 : 0);  // t-th slot not mine
+                    const unsigned off =
+                        t < fix_n - 1 ? (unsigned)((sl * (BM * BN) + 4 * tid) * 4) : 0xffffffffu;
+                    static_for<4>([&](auto Q) WPK_LAMBDA {
+                        constexpr int qd = decltype(Q)::value;
+                        part[u][qd] = __builtin_bit_cast(
+                            v4f, __builtin_amdgcn_raw_buffer_load_b128(srsrc, off, qd * 16 * T, kCoherent));
+                    });
+                });
+                static_for<8>([&](auto UQ) WPK_LAMBDA {
+                    constexpr int u = decltype(UQ)::value / 4, qd = decltype(UQ)::value % 4;
+                    acc[0][4 * qd] += part[u][qd][0];
+                    acc[0][4 * qd + 1] += part[u][qd][1];
+                    acc[0][4 * qd + 2] += part[u][qd][2];
+                    acc[0][4 * qd + 3] += part[u][qd][3];
+                });
+            }
+        } else {
+            for (int sl = 0; sl < fix_n; ++sl) {
+                if (sl == fix_slot) continue;
+                const int other = (sl * (BM * BN) + 4 * tid) * 4;
+                static_for<NNT * NMT * 4>([&](auto Q) WPK_LAMBDA {
+                    constexpr int qd = decltype(Q)::value, ij = qd / 4, e4 = qd % 4;
+                    v4f v = __builtin_bit_cast(
+                        v4f, __builtin_amdgcn_raw_buffer_load_b128(srsrc, other, qd * 16 * T, kCoherent));
+                    acc[ij][4 * e4] += v[0];
+                    acc[ij][4 * e4 + 1] += v[1];
+                    acc[ij][4 * e4 + 2] += v[2];
+                    acc[ij][4 * e4 + 3] += v[3];
+                });
+            }
         }
     }
     const bool atomic = mode == kAtomic;

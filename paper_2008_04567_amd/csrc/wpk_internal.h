@@ -20,6 +20,7 @@ extern const int32_t kWnVals[3];     // 1, 2, 4
 extern const int32_t kSplitVals[18]; // 1 .. 16, 20, 24
 extern const int32_t kRemapVals[2];  // 0, 1
 extern const int32_t kStageVals[3];   // 1, 2, 3 tiles in flight in registers
+extern const int32_t kReduceVals[2];  // 0 workspace, 1 atomics
 extern const int32_t kPersistVals[5]; // 0 (off), 1, 2, 3, 4 workgroups per compute unit
 extern const int kGeneCounts[WPK_N_GENES];
 const int32_t *gene_values(int g);

@@ -23,8 +23,8 @@ def main():
     ap.add_argument("--workload", default="config3",
                     help="config2|config3|config4|table1|resnet18_n1|resnet50_n1|resnet50_n16")
     ap.add_argument("--seeds", type=int, default=5)
-    ap.add_argument("--generations", type=int, default=8)
-    ap.add_argument("--population", type=int, default=48)
+    ap.add_argument("--generations", type=int, default=12)
+    ap.add_argument("--population", type=int, default=64)
     ap.add_argument("--max-layers", type=int, default=0, help="only the first so many distinct layers")
     args = ap.parse_args()
 
@@ -55,6 +55,7 @@ def main():
             for s in range(args.seeds):
                 opt = B.tune_default_options(mode=mode, refine=0, seed=1000 + s, patience=0, eps=0.0,
                                              max_generations=args.generations,
+                                             elites=max(1, args.population // 8),
                                              population=args.population,
                                              next_population=args.population,
                                              participants=args.population)

@@ -55,7 +55,7 @@ int main(void) {
                    ctypes.sizeof(B.TuneOptions), ctypes.sizeof(B.TuneReport),
                    B.TuneOptions.seed.offset, B.TuneOptions.min_group_us.offset,
                    B.TuneReport.best_us.offset, B.TuneReport.seconds.offset]
-    assert got[0] == 60 and got[1] == 36
+    assert got[0] == 60 and got[1] == 40
 
 
 def d13(n, c, h, w, k, r, s, st=(1, 1), pd=(0, 0), dl=(1, 1)):
@@ -118,7 +118,7 @@ def test_error_codes():
 
 def test_config_encoding_roundtrip_and_constraint_check():
     lo, hi = B.config_gene_ranges()
-    assert lo == [0] * 9 and hi == [2, 2, 2, 2, 2, 17, 1, 4, 2]
+    assert lo == [0] * 10 and hi == [2, 2, 2, 2, 2, 17, 1, 4, 2, 1]
     d = B.make_desc(W.config3()[1])
     legal = B.legal_configs(d)
     assert 3000 < len(legal) < 15000
@@ -143,6 +143,10 @@ def test_config_encoding_roundtrip_and_constraint_check():
     assert not B.config_legal(d, B.ConvConfig(128, 64, 16, 2, 2, 2, 0, 2, 2))   # persistent + split
     assert not B.config_legal(d, B.ConvConfig(128, 64, 16, 2, 2, 1, 1, 2, 2))   # persistent + remap
     assert not B.config_legal(d, B.ConvConfig(128, 64, 16, 2, 2, 1, 1, 0, 4))   # stages not in list
+    assert B.config_legal(d, B.make_config(128, 64, 16, 2, 2, split_k=3, reduce=1))
+    assert B.config_legal(d, B.make_config(128, 64, 16, 2, 2, persist=2, reduce=1))
+    assert not B.config_legal(d, B.make_config(128, 64, 16, 2, 2, reduce=1))   # nothing shared
+    assert not B.config_legal(d, B.make_config(128, 64, 16, 2, 2, split_k=3, reduce=2))
     assert B.legal_configs(d13(1, 1, 20, 20, 8, 17, 2)) == []                  # > 16 filter rows
     assert B.legal_configs(d13(1, 1, 20, 20, 8, 2, 16)) == []                  # > 15 filter columns
     assert B.legal_configs(d13(1, 1, 20, 20, 8, 16, 15)) != []
@@ -220,7 +224,7 @@ def test_engine_matches_oracle_generation_by_generation(seed, fit, cons):
 
 def test_engine_default_sizes_and_flat_fitness():
     opt = B.tune_default_options(seed=3)
-    ref = oga.genetic_search(LO, HI, lambda ch: True, fit_sep, seed=3, pop=48, elites=6, pm=0.15,
+    ref = oga.genetic_search(LO, HI, lambda ch: True, fit_sep, seed=3, pop=64, elites=8, pm=0.15,
                              eps=0.03, patience=5, max_gen=16)
     got = B.ga_search(LO, HI, None, fit_sep, opt, history_capacity=16)
     assert got["history"] == ref["history"]
@@ -232,7 +236,7 @@ def test_engine_random_mode_and_bad_arguments():
     opt = B.tune_default_options(seed=5, mode=1, max_generations=5, patience=0, eps=0.0)
     got = B.ga_search(LO, HI, None, fit_sep, opt, history_capacity=5)
     assert got["generations"] == 5
-    assert all(len(p) == 48 for p, _ in got["history"])
+    assert all(len(p) == 64 for p, _ in got["history"])
     with pytest.raises(B.WpkError):
         B.ga_search([0, 3], [1, 2], None, fit_sep)       # empty gene range
     with pytest.raises(B.WpkError):

@@ -61,7 +61,8 @@ def test_persistent_schedule():
         y_ref, d_ref = PT.oracle_full(l, x, w)
         for (bm, bn, bk, wm, wn) in [(64, 32, 16, 2, 1), (128, 64, 32, 4, 2), (64, 64, 8, 2, 1)]:
             for persist in (1, 2, 3, 4):
-                c = B.make_config(bm, bn, bk, wm, wn, persist=persist, stages=1 + persist % 3)
+                c = B.make_config(bm, bn, bk, wm, wn, persist=persist, stages=1 + persist % 3,
+                                  reduce=persist % 2)     # both ways of summing shared tiles
                 assert B.config_legal(desc, c)
                 print(l["name"], c, flush=True)
                 for again in range(2):
@@ -76,7 +77,8 @@ def test_split_k_and_remap_settings():
     for (bm, bn, bk, wm, wn) in [(128, 64, 16, 2, 2), (64, 64, 8, 2, 2), (256, 128, 32, 4, 2)]:
         for split in (2, 3, 5, 7, 8, 11, 16, 20, 24):
             for remap in (0, 1):
-                c = B.make_config(bm, bn, bk, wm, wn, split, remap, stages=1 + split % 3)
+                c = B.make_config(bm, bn, bk, wm, wn, split, remap, stages=1 + split % 3,
+                                  reduce=(split // 2) % 2)   # both ways of summing the slices
                 if not B.config_legal(desc, c):
                     continue
                 print(c, flush=True)
