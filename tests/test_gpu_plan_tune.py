@@ -81,6 +81,32 @@ def test_tuner_small_budget_result_is_legal_cached_and_correct():
     B.cache_clear()
 
 
+def test_genetic_search_against_exhaustive_and_random():
+    """On the real kernel family the space is small enough to enumerate: with the default sizes
+    the genetic search must land near the fastest member and must not lose to a random search of
+    the same number of generations (Section 3.2: the searches "consistently outperform random
+    search").  Margins allow for 1-2 % timing noise between two measurements of one candidate."""
+    B.cache_clear()
+    desc = B.make_desc(W.config3()[3])
+    _, ex = B.conv_tune_ex(desc, B.tune_default_options(mode=2, refine=0, reps=3), force=True)
+    ratios = {}
+    for label, mode in (("genetic", 0), ("random", 1)):
+        found = []
+        for seed in (11, 12, 13):
+            opt = B.tune_default_options(mode=mode, refine=0, seed=seed, patience=0, eps=0.0,
+                                         max_generations=12)
+            _, rep = B.conv_tune_ex(desc, opt, force=True)
+            assert rep.rejected == 0
+            found.append(rep.best_us / ex.best_us)
+        ratios[label] = found
+    print("exhaustive %.2f us over %d points; found/fastest" % (ex.best_us, ex.evaluations), ratios,
+          flush=True)
+    assert ex.rejected == 0 and ex.evaluations > 5000
+    assert np.mean(ratios["genetic"]) <= 1.05 and max(ratios["genetic"]) <= 1.10
+    assert np.mean(ratios["genetic"]) <= np.mean(ratios["random"]) + 0.03
+    B.cache_clear()
+
+
 def test_plan_fused_basic_block():
     """Two chained 3x3 layers of a residual block through a plan with fused epilogues:
     y1 = relu(conv(x, w1) + b1); y2 = relu(conv(y1, w2) + b2 + x).  The second layer is checked
