@@ -134,3 +134,23 @@ def conv2d_fused(shape, x, w, bias=None, residual=None, relu=False, threads=0):
     if relu:
         y = np.where(y > 0.0, y, 0.0)
     return y, d
+
+
+LAYOUTS = ("NCHW", "NHWC")
+
+
+def conv2d_layout(shape, x, w, x_layout="NCHW", y_layout="NCHW", threads=0):
+    """The same operator on activations stored channels-last (Section 2.1, data layout
+    transformation: the values are those of the definition, only their place in memory changes).
+
+    ``x`` is [N][C][H][W] or [N][H][W][C] as ``x_layout`` says, the result (value and normaliser)
+    [N][K][P][Q] or [N][P][Q][K] as ``y_layout`` says; weights stay [K][C][R][S].  A layout is a
+    permutation of indices, so the oracle permutes, runs the seven loops, and permutes back."""
+    assert x_layout in LAYOUTS and y_layout in LAYOUTS
+    x = np.asarray(x, dtype=np.float32)
+    if x_layout == "NHWC":
+        x = x.reshape(shape.n, shape.h, shape.w, shape.c).transpose(0, 3, 1, 2)
+    y, d, _ = conv2d(shape, np.ascontiguousarray(x), w, threads=threads)
+    if y_layout == "NHWC":
+        y, d = (np.ascontiguousarray(t.transpose(0, 2, 3, 1)) for t in (y, d))
+    return y, d

@@ -373,3 +373,66 @@ def test_fused_special_cases():
     assert y.min() == 0.0 and (z < 0).any() and np.array_equal(y[z > 0], z[z > 0])
     # residual addition commutes with the convolution's linearity: conv(x,w)+r == fused(r)
     assert np.array_equal(z, y0 + b.astype(np.float64)[None, :, None, None] + r.astype(np.float64))
+
+
+# ---- channels-last activations (Section 2.1, data layout transformation) ------------------------
+def _brute_nhwc(n_, c_, h_, w_, k_, r_, s_, st, pd, dl, x, w):
+    """Second evaluator, written on flat channels-last buffers with its own index arithmetic:
+    scatter form (every input element is pushed to the outputs it feeds)."""
+    p_ = (h_ + 2 * pd[0] - dl[0] * (r_ - 1) - 1) // st[0] + 1
+    q_ = (w_ + 2 * pd[1] - dl[1] * (s_ - 1) - 1) // st[1] + 1
+    xf, wf = np.asarray(x, np.float64).ravel(), np.asarray(w, np.float64).ravel()
+    y = np.zeros(n_ * p_ * q_ * k_)
+    for n in range(n_):
+        for hi in range(h_):
+            for wi in range(w_):
+                for c in range(c_):
+                    xv = xf[((n * h_ + hi) * w_ + wi) * c_ + c]
+                    for r in range(r_):
+                        ph = hi + pd[0] - r * dl[0]
+                        if ph % st[0] or not 0 <= ph // st[0] < p_:
+                            continue
+                        for s in range(s_):
+                            qw = wi + pd[1] - s * dl[1]
+                            if qw % st[1] or not 0 <= qw // st[1] < q_:
+                                continue
+                            base = ((n * p_ + ph // st[0]) * q_ + qw // st[1]) * k_
+                            for k in range(k_):
+                                y[base + k] += xv * wf[((k * c_ + c) * r_ + r) * s_ + s]
+    return y.reshape(n_, p_, q_, k_)
+
+
+@pytest.mark.parametrize("cfg", [
+    (2, 3, 5, 4, 2, 3, 2, (1, 1), (1, 0), (1, 1)),
+    (1, 4, 6, 5, 3, 2, 3, (2, 1), (0, 2), (1, 2)),
+    (2, 2, 7, 6, 3, 3, 3, (2, 3), (2, 1), (2, 1)),
+])
+def test_channels_last_against_flat_scatter_evaluator(cfg):
+    n_, c_, h_, w_, k_, r_, s_, st, pd, dl = cfg
+    rng = np.random.default_rng(hash(cfg) % 1000)
+    x = rng.uniform(-1, 1, (n_, h_, w_, c_)).astype(np.float32)          # channels last
+    w = rng.uniform(-1, 1, (k_, c_, r_, s_)).astype(np.float32)
+    sh = oc.make_shape(n_, c_, h_, w_, k_, r_, s_, st, pd, dl)
+    y, d = oc.conv2d_layout(sh, x, w, "NHWC", "NHWC")
+    ref = _brute_nhwc(n_, c_, h_, w_, k_, r_, s_, st, pd, dl, x, w)
+    assert y.shape == ref.shape
+    assert np.max(np.abs(y - ref)) <= 1e-12 * max(1.0, d.max())
+    # mixed layouts are the same values, permuted
+    y2, d2 = oc.conv2d_layout(sh, x, w, "NHWC", "NCHW")
+    assert np.array_equal(y2, y.transpose(0, 3, 1, 2)) and np.array_equal(d2, d.transpose(0, 3, 1, 2))
+    y3, _ = oc.conv2d_layout(sh, x.transpose(0, 3, 1, 2), w, "NCHW", "NHWC")
+    assert np.array_equal(y3, y)
+
+
+def test_channels_last_delta_and_channel_order():
+    # 1x1 identity weights: y == x in the same layout; a channel permutation in w permutes the
+    # last axis (the channel axis of a channels-last tensor), not a spatial one
+    rng = np.random.default_rng(8)
+    x = rng.uniform(-1, 1, (2, 5, 4, 6)).astype(np.float32)              # N H W C
+    sh = oc.make_shape(2, 6, 5, 4, 6, 1, 1)
+    eye = np.eye(6, dtype=np.float32).reshape(6, 6, 1, 1)
+    y, _ = oc.conv2d_layout(sh, x, eye, "NHWC", "NHWC")
+    assert np.array_equal(y, x.astype(np.float64))
+    perm = np.array([3, 0, 5, 1, 4, 2])
+    y, _ = oc.conv2d_layout(sh, x, eye[perm], "NHWC", "NHWC")
+    assert np.array_equal(y, x[..., perm].astype(np.float64))
