@@ -40,7 +40,7 @@ enum {
     WPK_OK            = 0,
     WPK_E_BAD_DESC    = -1, /* non-positive size/stride/dilation, negative pad, P<=0 or Q<=0      */
     WPK_E_NULL_PTR    = -2, /* a required pointer argument is NULL                                */
-    WPK_E_UNSUPPORTED = -3, /* dtype/layout other than fp32/NCHW, or a tensor beyond 2^30 elements */
+    WPK_E_UNSUPPORTED = -3, /* dtype other than fp32, layout value out of range, or a tensor beyond 2^30 elements */
     WPK_E_HIP         = -4, /* a HIP runtime call failed; wpk_last_hip_error() has the code       */
     WPK_E_NO_CONFIG   = -5, /* config id out of range, or not legal for this descriptor           */
     WPK_E_BAD_ARG     = -6, /* any other invalid argument (index out of range, bad sizes ...)     */
@@ -49,7 +49,12 @@ enum {
 };
 
 enum { WPK_F32 = 0 };
-enum { WPK_NCHW = 0 };
+/* Activation layouts.  Bit 0: x is channels-last [N][H][W][C]; bit 1: y (and a fused residual) is
+ * channels-last [N][P][Q][K].  Weights are always [K][C][R][S].  The two mixed values make the
+ * kernel that computes a layer also transform the layout (Section 2.1, data layout transformation)
+ * at no extra pass over memory.  The tiled family gathers channels-last x only when C is a
+ * multiple of the configuration's bk (and of 4); other shapes run on the direct kernel. */
+enum { WPK_NCHW = 0, WPK_X_NHWC = 1, WPK_Y_NHWC = 2, WPK_NHWC = 3 };
 
 /* ---- the convolution problem (Section 2.3 "State space", first nine observation entries) -- */
 typedef struct wpk_conv_desc {
@@ -59,7 +64,7 @@ typedef struct wpk_conv_desc {
     int32_t pad_h, pad_w;           /* >= 0, zeros added on both sides (VALID = 0)                */
     int32_t dil_h, dil_w;           /* >= 1                                                       */
     int32_t dtype;                  /* WPK_F32                                                    */
-    int32_t layout;                 /* WPK_NCHW                                                   */
+    int32_t layout;                 /* WPK_NCHW, WPK_NHWC, WPK_X_NHWC or WPK_Y_NHWC              */
 } wpk_conv_desc;
 
 /* Validate `d` and return the output extent.  p, q may be NULL.  Host only. */
@@ -228,7 +233,8 @@ int wpk_ga_search(int32_t n_genes, const int32_t *lo, const int32_t *hi,
 typedef struct wpk_plan wpk_plan;
 
 /* Build a plan for n_layers descriptors (host array).  Layers with identical descriptors share
- * one search.  `tune` = 0 uses cached/default configs, 1 runs wpk_conv_tune on cache misses.
+ * one search.  A layer outside the tiled family runs on the direct kernel; wpk_plan_layer_config
+ * reports it as an all-zero configuration.  `tune` = 0 uses cached/default configs, 1 runs wpk_conv_tune on cache misses.
  * Allocates device memory for packed weights and split-K needs; synchronises the device. */
 int wpk_conv_plan(const wpk_conv_desc *layers, int32_t n_layers, int32_t tune, wpk_plan **out);
 

@@ -11,6 +11,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libwpk.so")
 N_GENES = 10
+NCHW, X_NHWC, Y_NHWC, NHWC = 0, 1, 2, 3   # layout codes of ConvDesc.layout
 
 OK, E_BAD_DESC, E_NULL_PTR, E_UNSUPPORTED, E_HIP, E_NO_CONFIG, E_BAD_ARG, E_IO, E_VERIFY = (
     0, -1, -2, -3, -4, -5, -6, -7, -8)

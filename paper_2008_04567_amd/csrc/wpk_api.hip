@@ -40,9 +40,11 @@ static const LaunchFn kLaunch[] = {
 // ---- helper kernels ---------------------------------------------------------------------------------
 // w[K][CRS] -> wp[CRSpad/4][Kpad][4] (element (kk, k) at ((kk/4)*Kpad + k)*4 + kk%4), zero padded,
 // through a 32x32 LDS tile so both sides coalesce.
+// With RS > 0 the packed reduction index runs (r, s, c) instead of the source's (c, r, s): the
+// order the channels-last gather walks.
 __global__ void __launch_bounds__(256) pack_weights_kernel(const float *__restrict__ w,
                                                            float *__restrict__ wp, int K, int CRS,
-                                                           int Kpad)
+                                                           int Kpad, int C, int RS)
 {
     __shared__ float tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
@@ -50,7 +52,8 @@ __global__ void __launch_bounds__(256) pack_weights_kernel(const float *__restri
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int k = k0 + ty + i * 8, kk = kk0 + tx;
-        tile[ty + i * 8][tx] = (k < K && kk < CRS) ? w[(size_t)k * CRS + kk] : 0.0f;
+        int src = RS > 0 ? (kk % C) * RS + kk / C : kk;
+        tile[ty + i * 8][tx] = (k < K && kk < CRS) ? w[(size_t)k * CRS + src] : 0.0f;
     }
     __syncthreads();
     // a thread writes one quad: channel k0 + (t % 32), k quad kk0/4 + t/32
@@ -66,14 +69,22 @@ __global__ void __launch_bounds__(256) direct_conv_kernel(const float *__restric
                                                           float *__restrict__ dnorm,
                                                           wpk_conv_desc d, int P, int Q, long long total)
 {
+    const bool xl = d.layout & 1, yl = d.layout & 2;  // channels-last x / y
     for (long long o = (long long)blockIdx.x * blockDim.x + threadIdx.x; o < total;
          o += (long long)gridDim.x * blockDim.x) {
-        int q = (int)(o % Q);
-        long long t = o / Q;
-        int p = (int)(t % P);
-        t /= P;
-        int k = (int)(t % d.k);
-        long long n = t / d.k;
+        int q, p, k;
+        long long n, t = o;
+        if (yl) {
+            k = (int)(t % d.k); t /= d.k;
+            q = (int)(t % Q); t /= Q;
+            p = (int)(t % P);
+            n = t / P;
+        } else {
+            q = (int)(t % Q); t /= Q;
+            p = (int)(t % P); t /= P;
+            k = (int)(t % d.k);
+            n = t / d.k;
+        }
         float acc = 0.0f, mag = 0.0f;
         for (int c = 0; c < d.c; ++c)
             for (int r = 0; r < d.r; ++r) {
@@ -82,7 +93,8 @@ __global__ void __launch_bounds__(256) direct_conv_kernel(const float *__restric
                 for (int s = 0; s < d.s; ++s) {
                     int iw = q * d.stride_w - d.pad_w + s * d.dil_w;
                     if (iw < 0 || iw >= d.w) continue;
-                    float xv = x[((n * d.c + c) * d.h + ih) * (long long)d.w + iw];
+                    float xv = xl ? x[((n * d.h + ih) * (long long)d.w + iw) * d.c + c]
+                                  : x[((n * d.c + c) * d.h + ih) * (long long)d.w + iw];
                     float wv = w[(((long long)k * d.c + c) * d.r + r) * d.s + s];
                     acc = fmaf(xv, wv, acc);
                     mag += fabsf(xv * wv);
@@ -104,9 +116,15 @@ __global__ void fill_zero_kernel(float4 *__restrict__ p4, float *__restrict__ ta
 
 // Zero y for all pixels m >= m_begin (every channel): the tiles a persistent launch accumulates
 // into with atomics.  One lane per (channel, pixel), pixels fastest.
-__global__ void zero_pixels_kernel(float *__restrict__ y, int m_begin, int M, int K, int PQ)
+__global__ void zero_pixels_kernel(float *__restrict__ y, int m_begin, int M, int K, int PQ, int yl)
 {
     const long long span = M - m_begin;
+    if (yl) {  // channels-last: those pixels are one contiguous range
+        for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < span * K;
+             i += (long long)gridDim.x * blockDim.x)
+            y[(long long)m_begin * K + i] = 0.0f;
+        return;
+    }
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < span * K;
          i += (long long)gridDim.x * blockDim.x) {
         int m = m_begin + (int)(i % span), k = (int)(i / span);
@@ -118,12 +136,13 @@ __global__ void zero_pixels_kernel(float *__restrict__ y, int m_begin, int M, in
 // y = act(y + bias[k] + res): the fused epilogue as a pass of its own, for the launches that
 // cannot apply it while storing (atomic accumulation, the direct kernel).
 __global__ void epilogue_kernel(float *__restrict__ y, const float *__restrict__ bias,
-                                const float *__restrict__ res, int relu, int K, int PQ, long long total)
+                                const float *__restrict__ res, int relu, int K, int PQ, int yl,
+                                long long total)
 {
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
          i += (long long)gridDim.x * blockDim.x) {
         float v = y[i];
-        if (bias) v += bias[(i / PQ) % K];
+        if (bias) v += bias[yl ? i % K : (i / PQ) % K];
         if (res) v += res[i];
         if (relu) v = fmaxf(v, 0.0f);
         y[i] = v;
@@ -189,6 +208,18 @@ static std::vector<int32_t> build_tap_tables(const Problem &pr)
 {
     const wpk_conv_desc &d = pr.d;
     const int RS = d.r * d.s;
+    if (pr.xl) {
+        // channels-last: one entry per filter tap, {byte offset of the tap (biased like the
+        // descriptor base), mask bit of r | mask bit of s << 8}; padded to 32 entries
+        const int biasl = (d.pad_h * d.w + d.pad_w) * d.c * 4;
+        std::vector<int32_t> t((size_t)std::max(RS, 32) * 2, 0);
+        for (int rs = 0; rs < RS; ++rs) {
+            int r = rs / d.s, s = rs % d.s;
+            t[2 * rs] = ((r * d.dil_h - d.pad_h) * d.w + s * d.dil_w - d.pad_w) * d.c * 4 + biasl;
+            t[2 * rs + 1] = r | (16 + s) << 8;
+        }
+        return t;
+    }
     const int bias = (d.pad_h * d.w + d.pad_w) * 4;
     auto entry = [&](int c, int rs, int32_t *e) {
         int r = rs / d.s, s = rs % d.s;
@@ -233,7 +264,8 @@ static int upload_tap_table(const Problem &pr, int32_t **out)
 static int pack_weights(const Problem &pr, const float *w, float *wp, hipStream_t st)
 {
     dim3 grid(pr.CRSpad / 32, pr.Kpad / 32);
-    hipLaunchKernelGGL(pack_weights_kernel, grid, dim3(256), 0, st, w, wp, pr.d.k, pr.CRS, pr.Kpad);
+    hipLaunchKernelGGL(pack_weights_kernel, grid, dim3(256), 0, st, w, wp, pr.d.k, pr.CRS, pr.Kpad, pr.d.c,
+                       pr.xl ? pr.d.r * pr.d.s : 0);
     WPK_HIP(hipGetLastError());
     return WPK_OK;
 }
@@ -272,7 +304,7 @@ static int run_epilogue(const Problem &pr, const Epilogue &epi, float *y, hipStr
     if (!epi.any()) return WPK_OK;
     int blocks = (int)std::min<int64_t>(4096, (pr.y_elems + 255) / 256);
     hipLaunchKernelGGL(epilogue_kernel, dim3(blocks), dim3(256), 0, st, y, epi.bias, epi.res, epi.relu,
-                       pr.d.k, pr.P * pr.Q, (long long)pr.y_elems);
+                       pr.d.k, pr.P * pr.Q, pr.yl ? 1 : 0, (long long)pr.y_elems);
     WPK_HIP(hipGetLastError());
     return WPK_OK;
 }
@@ -330,7 +362,9 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     a.tiles_n = (d.k + cfg.bn - 1) / cfg.bn;
     a.remap = cfg.xcd_remap;
     a.x_bytes = (uint32_t)(pr.x_elems * 4);
-    a.x_bias = (uint32_t)((d.pad_h * d.w + d.pad_w) * 4);
+    a.x_bias = (uint32_t)((d.pad_h * d.w + d.pad_w) * 4 * (pr.xl ? d.c : 1));
+    a.xl = pr.xl ? 1 : 0;
+    a.yl = pr.yl ? 1 : 0;
     a.w_bytes = (uint32_t)((int64_t)pr.CRSpad * pr.Kpad * 4);
     a.y_bytes = (uint32_t)(pr.y_elems * 4);
     a.persist = cfg.persist;
@@ -366,7 +400,7 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
                 long long n = (long long)(a.M - m_begin) * a.K;
                 int blocks = (int)std::min<long long>(4096, (n + 255) / 256);
                 hipLaunchKernelGGL(zero_pixels_kernel, dim3(blocks), dim3(256), 0, st, y, m_begin, a.M,
-                                   a.K, a.PQ);
+                                   a.K, a.PQ, a.yl);
                 WPK_HIP(hipGetLastError());
             }
         }
@@ -607,6 +641,7 @@ struct wpk_plan {
         bool has_w;
         float *bias;  // library-owned copy of the layer's bias, or NULL
         int relu;
+        bool direct;  // outside the tiled family: wp holds plain [K][C][R][S] weights for the direct kernel
     };
     FixupBuf fix;  // fix-up workspace shared by the layers (they run one after another)
     std::vector<Layer> layers;
@@ -882,11 +917,19 @@ int wpk_conv_plan(const wpk_conv_desc *layers, int32_t n_layers, int32_t tune, w
         wpk_plan::Layer L;
         rc = make_problem(&layers[i], &L.pr);
         if (rc != WPK_OK) break;
-        if (!L.pr.tiled_ok) { rc = WPK_E_UNSUPPORTED; break; }
         L.wp = nullptr;
         L.has_w = false;
         L.bias = nullptr;
         L.relu = 0;
+        L.direct = !L.pr.tiled_ok;
+        if (L.direct) {  // oversized filter, or a channels-last shape the tiled gather does not take
+            memset(&L.cfg, 0, sizeof L.cfg);
+            L.unique = -1;
+            hipError_t e = hipMalloc((void **)&L.wp, (size_t)L.pr.w_elems * sizeof(float));
+            if (e != hipSuccess) { set_last_hip_error((int)e); rc = WPK_E_HIP; break; }
+            plan->layers.push_back(L);
+            continue;
+        }
         std::string key = desc_key(&layers[i]);
         auto it = seen.find(key);
         if (it == seen.end()) {
@@ -922,6 +965,12 @@ int wpk_plan_set_weights(wpk_plan *plan, int32_t layer, const float *w, void *st
     if (!plan || !w) return WPK_E_NULL_PTR;
     if (layer < 0 || layer >= (int)plan->layers.size()) return WPK_E_BAD_ARG;
     wpk_plan::Layer &L = plan->layers[layer];
+    if (L.direct) {
+        WPK_HIP(hipMemcpyAsync(L.wp, w, (size_t)L.pr.w_elems * sizeof(float), hipMemcpyDeviceToDevice,
+                               (hipStream_t)stream));
+        L.has_w = true;
+        return WPK_OK;
+    }
     int rc = pack_weights(L.pr, w, L.wp, (hipStream_t)stream);
     if (rc == WPK_OK) L.has_w = true;
     return rc;
@@ -953,6 +1002,10 @@ int wpk_plan_run_layer_fused(wpk_plan *plan, int32_t layer, const float *x, cons
     if (!L.has_w) return WPK_E_BAD_ARG;
     Epilogue epi;
     epi.bias = L.bias; epi.res = residual; epi.relu = L.relu;
+    if (L.direct) {
+        int rc = run_ref(L.pr, x, L.wp, y, nullptr, (hipStream_t)stream);
+        return rc != WPK_OK ? rc : run_epilogue(L.pr, epi, y, (hipStream_t)stream);
+    }
     return run_config(L.pr, L.cfg, plan->ktabs[L.unique], x, L.wp, y, &plan->fix, (hipStream_t)stream,
                       epi);
 }
@@ -994,7 +1047,7 @@ int wpk_plan_set_layer_config(wpk_plan *plan, int32_t layer, const wpk_conv_conf
 {
     if (!plan || !cfg) return WPK_E_NULL_PTR;
     if (layer < 0 || layer >= (int)plan->layers.size()) return WPK_E_BAD_ARG;
-    if (!legal_for(plan->layers[layer].pr, *cfg)) return WPK_E_NO_CONFIG;
+    if (plan->layers[layer].direct || !legal_for(plan->layers[layer].pr, *cfg)) return WPK_E_NO_CONFIG;
     FixupNeed need = fixup_need(plan->layers[layer].pr, *cfg, g_cus);
     if (need.bytes > (int64_t)plan->fix.bytes) {
         WPK_HIP(hipDeviceSynchronize());  // the old workspace may still be in use

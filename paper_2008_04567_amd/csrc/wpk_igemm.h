@@ -73,7 +73,15 @@ typedef const int __attribute__((address_space(4))) *tap_ptr;
 // LDS row pitch (floats) of a reduction-contiguous tile with BK k values per column.
 __host__ __device__ constexpr int lds_pitch(int bk) { return bk + 4; }
 
-template <int BM, int BN, int BK, int WM, int WN, int PD>
+// XL = 0: activations [N][C][H][W], reduction rows ordered (c, r, s) as described above.
+// XL = 1: activations channels-last, [N][H][W][C], reduction rows ordered (r, s, c) and C a
+//   multiple of BK.  A lane still owns one output pixel; four consecutive reduction rows are four
+//   consecutive channels of one tap, i.e. 16 contiguous bytes: one buffer_load_dwordx4 per quad.
+//   A step lies inside a single tap (r, s), so one table entry per step gives the tap's byte
+//   offset and mask bits, the channel offset is added on the scalar unit, and there are no
+//   padding rows.  Everything downstream of the staging registers is shared.
+// The layout of y (and of a fused residual) is a run-time flag of the epilogue (a.yl).
+template <int BM, int BN, int BK, int WM, int WN, int PD, int XL>
 __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
 {
     constexpr int T = 64 * WM * WN;
@@ -147,7 +155,8 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
             int n = m / a.PQ, pq = m - n * a.PQ;
             int p = pq / a.Q, q = pq - p * a.Q;
             int ih0 = p * a.stride_h - a.pad_h, iw0 = q * a.stride_w - a.pad_w;
-            xvoff[i] = ((n * a.C * a.H + p * a.stride_h) * a.W + q * a.stride_w) * 4;
+            xvoff[i] = XL ? ((n * a.H + p * a.stride_h) * a.W + q * a.stride_w) * a.C * 4
+                          : ((n * a.C * a.H + p * a.stride_h) * a.W + q * a.stride_w) * 4;
             unsigned inv = 0x80000000u;
             for (int r = 0; r < a.R; ++r) {
                 int ih = ih0 + r * a.dil_h;
@@ -167,6 +176,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     constexpr int NX = XP * XR;   // activation dwords per thread and tile
     constexpr int NXQ = NX / 4;   // ... stored to LDS as quads
     constexpr int NW = WL;        // weight quads per thread and tile
+    constexpr int NXL = XL ? NXQ : NX;  // activation load instructions per thread and tile
     float xr[PD * NX];
     v4f wr[PD * NW];
     int tap_off[XR], tap_rs[XR];  // wave-uniform: live in scalar registers
@@ -179,10 +189,24 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     // The last step of the reduction is the only one with padding rows past C*R*S; it reads a
     // separate 32-row table with exact entries.  Steps are visited in increasing order inside a
     // segment, so (c0, phase) advance incrementally.
+    // Channels-last: tap_c0 is the tap index rs of the step and tap_phase its first channel; the
+    // table has one entry per tap, {byte offset of the tap, mask bits}, and tap_cbase carries
+    // the channel offset.
     int tap_cbase = 0;  // channel base of the tile whose taps are loaded, added at the use
-    int tap_c0 = (kbeg * BK) / a.RS;
-    int tap_phase = kbeg * BK - tap_c0 * a.RS;
+    int tap_c0 = XL ? (kbeg * BK) / a.C : (kbeg * BK) / a.RS;
+    int tap_phase = XL ? kbeg * BK - tap_c0 * a.C : kbeg * BK - tap_c0 * a.RS;
     auto load_taps = [&](int step) WPK_LAMBDA {
+        if constexpr (XL) {
+            tap_off[0] = taps[2 * tap_c0];
+            tap_rs[0] = taps[2 * tap_c0 + 1];
+            tap_cbase = (tap_phase + rg * XR) * 4;
+            tap_phase += BK;
+            if (tap_phase >= a.C) {
+                tap_phase = 0;
+                tap_c0 += 1;
+            }
+            return;
+        }
         const bool last = step == a.nsteps - 1;
         tap_ptr tp = last ? (tap_ptr)(unsigned long long)a.ttab + 2 * (rg * XR)
                           : taps + 2 * (tap_phase * 32 + rg * XR);
@@ -201,6 +225,20 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     };
     // global -> register set SET: activation dword E of the tile whose taps are loaded
     auto load_x = [&](auto SET, auto E) WPK_LAMBDA {
+        if constexpr (XL) {  // E counts quads: pixel i, quad j4 of this thread's XR rows
+            constexpr int set = decltype(SET)::value, e = decltype(E)::value;
+            constexpr int i = e / (XR / 4), j4 = e % (XR / 4), b = set * NX + i * XR + 4 * j4;
+            int bad = __builtin_amdgcn_sbfe((int)xinv[i], tap_rs[0] & 0xff, 1) |
+                      __builtin_amdgcn_sbfe((int)xinv[i], tap_rs[0] >> 8, 1);  // 0 or all ones
+            v4f v = __builtin_bit_cast(
+                v4f, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, xvoff[i] | bad,
+                                                           tap_off[0] + tap_cbase + 16 * j4, 0));
+            xr[b] = v[0];
+            xr[b + 1] = v[1];
+            xr[b + 2] = v[2];
+            xr[b + 3] = v[3];
+            return;
+        }
         constexpr int set = decltype(SET)::value, e = decltype(E)::value, i = e / XR, jj = e % XR;
         int bad = __builtin_amdgcn_sbfe((int)xinv[i], tap_rs[jj] & 0xff, 1) |
                   __builtin_amdgcn_sbfe((int)xinv[i], tap_rs[jj] >> 8, 1);  // 0 or all ones
@@ -230,7 +268,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     };
     auto load_tile = [&](auto SET, int step) WPK_LAMBDA {
         load_taps(step);
-        static_for<NX>([&](auto E) WPK_LAMBDA { load_x(SET, E); });
+        static_for<NXL>([&](auto E) WPK_LAMBDA { load_x(SET, E); });
         static_for<NW>([&](auto E) WPK_LAMBDA { load_w(SET, step, E); });
     };
     auto store_tile = [&](auto SET, int buf) WPK_LAMBDA {
@@ -252,7 +290,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     // The last steps of a segment (no more tiles to load or store) run the plain form, with
     // whatever store and load is left done up front.  One barrier per step, at its end.
     constexpr int NM = (BK / 2) * NNT * NMT;       // MFMAs per step and wave
-    constexpr int NIT = NXQ + NW + NX + NW;        // stores (x, w) then loads (x, w)
+    constexpr int NIT = NXQ + NW + NXL + NW;       // stores (x, w) then loads (x, w)
     // the first load item must not come before the scalar tap loads it depends on
     static_assert(((NXQ + NW) * NM + NIT - 1) / NIT >= NNT * NMT, "taps are loaded too late");
     auto step_body = [&](const int r, auto SET, auto INTERLEAVE) WPK_LAMBDA {
@@ -306,10 +344,10 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                             store_x(SET, cur ^ 1, std::integral_constant<int, it>{});
                         else if constexpr (it < NXQ + NW)
                             store_w(SET, cur ^ 1, std::integral_constant<int, it - NXQ>{});
-                        else if constexpr (it < NXQ + NW + NX)
+                        else if constexpr (it < NXQ + NW + NXL)
                             load_x(SET, std::integral_constant<int, it - NXQ - NW>{});
                         else
-                            load_w(SET, kbeg + r + 1 + PD, std::integral_constant<int, it - NXQ - NW - NX>{});
+                            load_w(SET, kbeg + r + 1 + PD, std::integral_constant<int, it - NXQ - NW - NXL>{});
                     });
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -429,7 +467,8 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     //      whose loads return 0. ------------------------------------------------------------------
     const __amdgpu_buffer_rsrc_t yrsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.y, 0, (int)a.y_bytes, 0x00020000);
-    const int PQ4 = a.PQ * 4;
+    // y[n][k][p][q]: consecutive channels are PQ elements apart; channels-last y[n][p][q][k]: 1
+    const int PQ4 = a.yl ? 4 : a.PQ * 4;
     static_for<NMT>([&](auto J) WPK_LAMBDA {
         constexpr int j = decltype(J)::value;
         int m = m0 + wave_m * TM + j * 32 + lcol;
@@ -440,7 +479,8 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                 const int kbase = n0 + wave_n * TN + i * 32 + 4 * lrow;  // + 8*(e/4) + e%4
                 // byte offset of (n, kbase, pq) in y; only used for channels below K, where it
                 // is below y_bytes < 2^32
-                const unsigned voff = (unsigned)((((size_t)n * a.K + kbase) * a.PQ + pq) * 4);
+                const unsigned voff = a.yl ? (unsigned)(((size_t)m * a.K + kbase) * 4)
+                                           : (unsigned)((((size_t)n * a.K + kbase) * a.PQ + pq) * 4);
                 if (fused) {
                     const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
                         (void *)(a.bias ? a.bias : a.y), 0, a.bias ? a.K * 4 : 0, 0x00020000);
@@ -468,11 +508,12 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                         }
                     });
                 } else if (atomic) {
-                    float *yp = a.y + (size_t)n * a.K * a.PQ + pq;
+                    float *yp = a.yl ? a.y + (size_t)m * a.K : a.y + (size_t)n * a.K * a.PQ + pq;
+                    const size_t ks = a.yl ? 1 : (size_t)a.PQ;
                     static_for<16>([&](auto E) WPK_LAMBDA {
                         constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
                         if (kbase + de < a.K)
-                            unsafeAtomicAdd(yp + (size_t)(kbase + de) * a.PQ, acc[i * NMT + j][e]);
+                            unsafeAtomicAdd(yp + (size_t)(kbase + de) * ks, acc[i * NMT + j][e]);
                     });
                 } else {
                     static_for<16>([&](auto E) WPK_LAMBDA {
@@ -557,7 +598,10 @@ template <int BM, int BN, int BK, int WM, int WN, int PD>
 hipError_t launch_igemm(const IgemmArgs &a, hipStream_t stream)
 {
     dim3 grid((unsigned)(a.persist > 0 ? a.grid_persist : a.tiles_m * a.tiles_n * a.split_k));
-    hipLaunchKernelGGL((igemm_kernel<BM, BN, BK, WM, WN, PD>), grid, dim3(64 * WM * WN), 0, stream, a);
+    if (a.xl)
+        hipLaunchKernelGGL((igemm_kernel<BM, BN, BK, WM, WN, PD, 1>), grid, dim3(64 * WM * WN), 0, stream, a);
+    else
+        hipLaunchKernelGGL((igemm_kernel<BM, BN, BK, WM, WN, PD, 0>), grid, dim3(64 * WM * WN), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -62,6 +62,7 @@ struct Problem {
     int32_t Kpad;    // K rounded up to kKoutAlign
     int64_t x_elems, w_elems, y_elems;
     bool tiled_ok;   // the tiled family can run it (else only the direct kernel)
+    bool xl, yl;     // x / y channels-last (bits 0 and 1 of the descriptor's layout)
 };
 int make_problem(const wpk_conv_desc *d, Problem *out);  // WPK_OK or a WPK_E_* code
 std::string desc_key(const wpk_conv_desc *d);
@@ -95,6 +96,7 @@ struct IgemmArgs {
     const float *bias;  // [K] or NULL
     const float *res;   // laid out like y, or NULL
     int32_t relu;       // act = max(., 0) when nonzero
+    int32_t xl, yl;     // 1: x / y (and the residual) are channels-last
 };
 
 // What follows the convolution inside the same launch (Section 2.1, operator fusion).

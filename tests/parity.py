@@ -87,3 +87,45 @@ def check_layer(layer, cfg=None, mode="fwd", what=None):
     y_ref, d_ref = oracle_full(layer, x, w)
     y = run_gpu(layer, x, w, cfg=cfg, mode=mode)
     return assert_close(y, y_ref, d_ref, what or layer["name"])
+
+
+LAYOUT_NAMES = {0: ("NCHW", "NCHW"), 1: ("NHWC", "NCHW"), 2: ("NCHW", "NHWC"), 3: ("NHWC", "NHWC")}
+
+
+def check_layout(layer, layout, cfg=None, bias=None, residual=None, relu=False, what=None):
+    """One convolution with activations in the given layout code (bit 0: x channels-last, bit 1:
+    y and the residual channels-last) against the oracle in the same layouts.  ``layer`` and the
+    seeded inputs are the usual NCHW ones; the host permutes them."""
+    torch, dev = torch_dev()
+    xl, yl = LAYOUT_NAMES[layout]
+    x, w = W.make_inputs(layer)
+    desc = B.make_desc(layer, layout=layout)
+    P, Q = B.conv_out_shape(desc)
+    x_host = np.ascontiguousarray(x.transpose(0, 2, 3, 1)) if xl == "NHWC" else x
+    res_host = None
+    if residual is not None:    # given as [N][K][P][Q]
+        res_host = np.ascontiguousarray(residual.transpose(0, 2, 3, 1)) if yl == "NHWC" else residual
+    sh = oc.shape_from_layer(layer)
+    y_ref, d_ref = oc.conv2d_layout(sh, x_host, w, xl, yl)
+    if bias is not None or residual is not None or relu:
+        b64 = np.zeros(layer["k"]) if bias is None else bias.astype(np.float64)
+        bshape = (1, 1, 1, -1) if yl == "NHWC" else (1, -1, 1, 1)
+        y_ref = y_ref + b64.reshape(bshape)
+        d_ref = d_ref + np.abs(b64).reshape(bshape)
+        if res_host is not None:
+            y_ref = y_ref + res_host.astype(np.float64)
+            d_ref = d_ref + np.abs(res_host.astype(np.float64))
+        if relu:
+            y_ref = np.maximum(y_ref, 0.0)
+    n_out = y_ref.size
+    guard = 256
+    buf = torch.full((n_out + 2 * guard,), 12345.0, device=dev, dtype=torch.float32)
+    yd = buf[guard:guard + n_out]
+    B.conv2d_fwd_fused(desc, to_dev(x_host), to_dev(w), yd, bias=None if bias is None else to_dev(bias),
+                       residual=None if res_host is None else to_dev(res_host), relu=relu, cfg=cfg)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    assert np.all(host[:guard] == 12345.0) and np.all(host[guard + n_out:] == 12345.0), \
+        "write outside the output tensor"
+    return assert_close(host[guard:guard + n_out], y_ref, d_ref,
+                        what or "%s layout %d %r" % (layer["name"], layout, cfg))

@@ -104,8 +104,12 @@ def test_error_codes():
     bad.dtype = 1
     assert L.wpk_conv_out_shape(ctypes.byref(bad), None, None) == B.E_UNSUPPORTED
     bad = d13(1, 4, 8, 8, 4, 3, 3)
-    bad.layout = 1
+    bad.layout = 4
     assert L.wpk_conv_out_shape(ctypes.byref(bad), None, None) == B.E_UNSUPPORTED
+    for layout in (B.NCHW, B.X_NHWC, B.Y_NHWC, B.NHWC):
+        ok = d13(1, 4, 8, 8, 4, 3, 3)
+        ok.layout = layout
+        assert L.wpk_conv_out_shape(ctypes.byref(ok), None, None) == 0
     # null tensors are rejected before anything touches the GPU
     assert L.wpk_conv2d_fwd(ctypes.byref(good), None, None, None, None) == B.E_NULL_PTR
     assert L.wpk_conv2d_ref(ctypes.byref(good), None, None, None, None) == B.E_NULL_PTR
@@ -150,6 +154,12 @@ def test_config_encoding_roundtrip_and_constraint_check():
     assert B.legal_configs(d13(1, 1, 20, 20, 8, 17, 2)) == []                  # > 16 filter rows
     assert B.legal_configs(d13(1, 1, 20, 20, 8, 2, 16)) == []                  # > 15 filter columns
     assert B.legal_configs(d13(1, 1, 20, 20, 8, 16, 15)) != []
+    # channels-last x: a step of bk reduction rows must lie inside one tap, so bk divides C
+    cl = B.make_desc(W.layer("cl", 1, 24, 12, 20, 3, 1, 1), layout=B.NHWC)
+    assert {c.bk for c in B.legal_configs(cl)} == {8}
+    assert B.legal_configs(B.make_desc(W.layer("cl", 1, 20, 12, 20, 3, 1, 1), layout=B.X_NHWC)) == []
+    assert {c.bk for c in B.legal_configs(B.make_desc(W.layer("cl", 1, 20, 12, 20, 3, 1, 1),
+                                                      layout=B.Y_NHWC))} == {8, 16, 32}
     with pytest.raises(B.WpkError):
         B.config_from_id(10 ** 9)
     with pytest.raises(B.WpkError):

@@ -222,6 +222,77 @@ def test_fused_epilogue_rectifier_bites_and_full_size():
     PT.assert_close(y.reshape(-1)[idx], np.maximum(z, 0.0), d, "config 3 layer fused")
 
 
+# channels-last: C = 32 so that every K-step of the family divides it; same ragged pixel and channel
+# tails as RAGGED
+RAGGED_CL = W.layer("ragged_cl", 2, 32, (19, 23), 72, 3, 1, 1, x_dist="u11", w_dist="u11", seed=79)
+
+
+def test_channels_last_every_tile_combination():
+    desc = B.make_desc(RAGGED_CL, layout=B.NHWC)
+    cfgs = B.legal_configs(desc, split_k=[1], xcd_remap=1, persist=[0])
+    assert len(cfgs) >= 120
+    for c in cfgs:
+        print(c, flush=True)
+        PT.check_layout(RAGGED_CL, B.NHWC, cfg=c)
+
+
+def test_channels_last_layouts_schedules_and_epilogue():
+    """All four layout codes (the mixed ones transform the layout in the same launch), through
+    plain, split and persistent schedules with both ways of summing shared tiles, with and
+    without the fused epilogue; then the default entry point."""
+    l = RAGGED_CL
+    P, Q = B.conv_out_shape(B.make_desc(l))
+    rng = np.random.default_rng(21)
+    bias = rng.uniform(-1, 1, l["k"]).astype(np.float32)
+    res = rng.uniform(-2, 2, (l["n"], l["k"], P, Q)).astype(np.float32)
+    cfgs = [B.make_config(64, 32, 16, 2, 1), B.make_config(128, 64, 16, 2, 2, 5),
+            B.make_config(128, 64, 32, 4, 2, 3, reduce=1), B.make_config(64, 64, 8, 2, 1, persist=2),
+            B.make_config(128, 128, 32, 2, 2, persist=1, reduce=1), None]
+    for layout in (B.NHWC, B.X_NHWC, B.Y_NHWC):
+        desc = B.make_desc(l, layout=layout)
+        for c in cfgs:
+            assert c is None or B.config_legal(desc, c), c
+            print(layout, c, flush=True)
+            PT.check_layout(l, layout, cfg=c)
+            PT.check_layout(l, layout, cfg=c, bias=bias, residual=res, relu=True)
+
+
+CL_SWEEP = [
+    # name, n, c, hw, k, rs, stride, pad, dil
+    ("cl_s2", 2, 16, (17, 15), 9, 3, 2, 1, 1),
+    ("cl_1x1", 2, 40, (9, 11), 36, 1, 1, 0, 1),
+    ("cl_1x1_s2", 2, 64, (14, 14), 48, 1, 2, 0, 1),
+    ("cl_5x3_dil", 1, 8, (21, 19), 10, (5, 3), (1, 2), (4, 2), (2, 2)),
+    ("cl_stem_like", 1, 8, (40, 40), 16, 7, 2, 3, 1),
+    ("cl_c24", 1, 24, (12, 12), 20, 3, 1, 1, 1),
+    ("cl_tiny", 1, 8, (5, 5), 3, 3, 1, 1, 1),
+]
+
+
+@pytest.mark.parametrize("case", CL_SWEEP, ids=lambda c: c[0])
+def test_channels_last_shape_sweep(case):
+    name, n, c, hw, k, rs, stride, pad, dil = case
+    l = W.layer(name, n, c, hw, k, rs, stride, pad, dil, x_dist="u11", w_dist="u11", seed=31)
+    desc = B.make_desc(l, layout=B.NHWC)
+    PT.check_layout(l, B.NHWC)
+    for c_ in [B.make_config(64, 32, 8, 2, 1), B.make_config(128, 128, 16, 2, 2),
+               B.make_config(256, 64, 32, 4, 1, stages=3), B.make_config(128, 64, 8, 2, 2, 2, 0, stages=1),
+               B.make_config(64, 64, 32, 2, 2, persist=2, stages=3)]:
+        if B.config_legal(desc, c_):
+            print(name, c_, flush=True)
+            PT.check_layout(l, B.NHWC, cfg=c_)
+
+
+def test_channels_last_shapes_outside_the_tiled_gather_use_the_direct_kernel():
+    # 3 input channels (an image): no K-step divides C, so no tiled configuration is legal
+    l = W.layer("cl_rgb", 1, 3, (30, 28), 16, 7, 2, 3, 1, x_dist="u11", w_dist="u11", seed=33)
+    for layout in (B.NHWC, B.X_NHWC):
+        assert B.legal_configs(B.make_desc(l, layout=layout)) == []
+        PT.check_layout(l, layout)
+    assert B.legal_configs(B.make_desc(l, layout=B.Y_NHWC)) != []       # x is NCHW: tiled
+    PT.check_layout(l, B.Y_NHWC)
+
+
 def test_oversized_filter_uses_the_direct_kernel():
     # the tiled family tracks at most 16 filter rows and 15 filter columns per pixel
     for rs in [(17, 2), (2, 16)]:
