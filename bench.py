@@ -99,6 +99,9 @@ def main():
     ap.add_argument("--workspace-limit", type=int, default=None,
                     help="bytes; wpk_set_workspace_limit before tuning (0: atomics instead of a workspace)")
     ap.add_argument("--refine", type=int, default=None, help="refinement rounds of the tuner")
+    ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc", "x_nhwc", "y_nhwc"],
+                    help="activation layout: channels-last x and y, or one of the two mixed forms "
+                         "(the convolution then also transforms the layout)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device copy (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -114,7 +117,8 @@ def main():
     dev = torch.device("cuda:0")
     dev_name, cus = B.device_info()
     layers, wl_text = workload_layers(W, args.workload)
-    descs = [B.make_desc(l) for l in layers]
+    layout = {"nchw": B.NCHW, "nhwc": B.NHWC, "x_nhwc": B.X_NHWC, "y_nhwc": B.Y_NHWC}[args.layout]
+    descs = [B.make_desc(l, layout=layout) for l in layers]
     log("device %s, %d CUs; workload %s" % (dev_name, cus, wl_text))
 
     if args.workspace_limit is not None:
@@ -133,7 +137,13 @@ def main():
                 continue
             seen.add(key)
             hit = B.cache_lookup(d) is not None
-            cid, rep = B.conv_tune_ex(d, opt, force=False)
+            try:
+                cid, rep = B.conv_tune_ex(d, opt, force=False)
+            except B.WpkError as e:
+                if e.status != B.E_UNSUPPORTED:
+                    raise
+                log("%-28s outside the tiled family: direct kernel" % l["name"])
+                continue
             if not hit:
                 log("tuned %-28s %-30s split %2d remap %d persist %d reduce %d: %8.2f us (default %8.2f us), "
                     "%d evals, %d gens, %.1f s" % (l["name"], B.config_kernel_name(rep.best),
@@ -162,7 +172,7 @@ def main():
     for i, (l, d) in enumerate(zip(layers, descs)):
         x, w = W.make_inputs(l)
         P, Q = B.conv_out_shape(d)
-        xh = torch.from_numpy(x)
+        xh = torch.from_numpy(np.ascontiguousarray(x.transpose(0, 2, 3, 1)) if layout & 1 else x)
         for c in range(copies):
             xs[c].append(xh.to(dev))
             ys[c].append(torch.empty((l["n"], l["k"], P, Q), device=dev, dtype=torch.float32))
@@ -251,7 +261,8 @@ def main():
                       "tune_seconds": round(t_tune, 1),
                       "activations": "rotated through %d copies (read from HBM)" % copies if args.cold
                                      else "one set, resident in the memory-side cache between passes",
-                      "epilogue": "fused: " + "+".join(sorted(epi)) if epi else "none"},
+                      "epilogue": "fused: " + "+".join(sorted(epi)) if epi else "none",
+                      "layout": args.layout},
            "pct_fp32_mfma_peak": round(100 * value / FP32_MFMA_PEAK_TFLOPS, 2),
            "roofline": roofline, "layers": rows}
     if args.calibrate_copy:

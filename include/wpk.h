@@ -52,8 +52,8 @@ enum { WPK_F32 = 0 };
 /* Activation layouts.  Bit 0: x is channels-last [N][H][W][C]; bit 1: y (and a fused residual) is
  * channels-last [N][P][Q][K].  Weights are always [K][C][R][S].  The two mixed values make the
  * kernel that computes a layer also transform the layout (Section 2.1, data layout transformation)
- * at no extra pass over memory.  The tiled family gathers channels-last x only when C is a
- * multiple of the configuration's bk (and of 4); other shapes run on the direct kernel. */
+ * at no extra pass over memory.  Channels-last x is gathered in 16-byte channel quads when C is a
+ * multiple of 32, row by row otherwise. */
 enum { WPK_NCHW = 0, WPK_X_NHWC = 1, WPK_Y_NHWC = 2, WPK_NHWC = 3 };
 
 /* ---- the convolution problem (Section 2.3 "State space", first nine observation entries) -- */

@@ -208,8 +208,8 @@ static std::vector<int32_t> build_tap_tables(const Problem &pr)
 {
     const wpk_conv_desc &d = pr.d;
     const int RS = d.r * d.s;
-    if (pr.xl) {
-        // channels-last: one entry per filter tap, {byte offset of the tap (biased like the
+    if (pr.xquad) {
+        // channels-last in channel quads: one entry per filter tap, {byte offset of the tap (biased like the
         // descriptor base), mask bit of r | mask bit of s << 8}; padded to 32 entries
         const int biasl = (d.pad_h * d.w + d.pad_w) * d.c * 4;
         std::vector<int32_t> t((size_t)std::max(RS, 32) * 2, 0);
@@ -220,10 +220,12 @@ static std::vector<int32_t> build_tap_tables(const Problem &pr)
         }
         return t;
     }
-    const int bias = (d.pad_h * d.w + d.pad_w) * 4;
+    // element strides of x: between channels, between pixels of a row (channels-last: 1 and C)
+    const int cs = pr.xl ? 1 : d.h * d.w, ps = pr.xl ? d.c : 1;
+    const int bias = (d.pad_h * d.w + d.pad_w) * ps * 4;
     auto entry = [&](int c, int rs, int32_t *e) {
         int r = rs / d.s, s = rs % d.s;
-        e[0] = (c * d.h * d.w + (r * d.dil_h - d.pad_h) * d.w + s * d.dil_w - d.pad_w) * 4 + bias;
+        e[0] = (c * cs + ((r * d.dil_h - d.pad_h) * d.w + s * d.dil_w - d.pad_w) * ps) * 4 + bias;
         e[1] = r | (16 + s) << 8;
     };
     std::vector<int32_t> t((size_t)(RS + 3) * 32 * 2, 0);
@@ -265,7 +267,7 @@ static int pack_weights(const Problem &pr, const float *w, float *wp, hipStream_
 {
     dim3 grid(pr.CRSpad / 32, pr.Kpad / 32);
     hipLaunchKernelGGL(pack_weights_kernel, grid, dim3(256), 0, st, w, wp, pr.d.k, pr.CRS, pr.Kpad, pr.d.c,
-                       pr.xl ? pr.d.r * pr.d.s : 0);
+                       pr.xquad ? pr.d.r * pr.d.s : 0);
     WPK_HIP(hipGetLastError());
     return WPK_OK;
 }
@@ -346,7 +348,7 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     IgemmArgs a;
     a.x = x; a.wp = wp; a.y = y; a.ktab = ktab;
     a.RS = d.r * d.s;
-    a.HW4 = d.h * d.w * 4;
+    a.HW4 = pr.xl ? 4 : d.h * d.w * 4;  // byte stride between channels of x
     a.bk_div_rs = cfg.bk / a.RS;
     a.bk_mod_rs = cfg.bk % a.RS;
     a.ttab = ktab + ((size_t)a.RS + (cfg.bk == 8 ? 0 : cfg.bk == 16 ? 1 : 2)) * 32 * 2;
@@ -363,8 +365,12 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     a.remap = cfg.xcd_remap;
     a.x_bytes = (uint32_t)(pr.x_elems * 4);
     a.x_bias = (uint32_t)((d.pad_h * d.w + d.pad_w) * 4 * (pr.xl ? d.c : 1));
-    a.xl = pr.xl ? 1 : 0;
+    a.xl = pr.xquad ? 2 : pr.xl ? 1 : 0;
     a.yl = pr.yl ? 1 : 0;
+    // whole channel quads with 16-byte stores when the tensors allow it
+    if (pr.yl && d.k % 4 == 0 && ((uintptr_t)y & 15) == 0 && ((uintptr_t)epi.res & 15) == 0 &&
+        ((uintptr_t)epi.bias & 15) == 0)
+        a.yl = 2;
     a.w_bytes = (uint32_t)((int64_t)pr.CRSpad * pr.Kpad * 4);
     a.y_bytes = (uint32_t)(pr.y_elems * 4);
     a.persist = cfg.persist;

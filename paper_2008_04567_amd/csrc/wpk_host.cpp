@@ -106,12 +106,12 @@ int make_problem(const wpk_conv_desc *d, Problem *out)
     pr.CRSpad = (int32_t)((crs + kRedAlign - 1) / kRedAlign * kRedAlign);
     pr.Kpad = (d->k + kKoutAlign - 1) / kKoutAlign * kKoutAlign;
     pr.xl = (d->layout & 1) != 0;
+    pr.xquad = pr.xl && d->c % kRedAlign == 0;
     pr.yl = (d->layout & 2) != 0;
     int64_t bias = ((int64_t)d->pad_h * d->w + d->pad_w) * 4 * (pr.xl ? d->c : 1);
     pr.tiled_ok = d->r <= kMaxFilterRows && d->s <= kMaxFilterCols &&
                   pr.x_elems * 4 + bias <= kMaxTiledBytes &&
-                  pr.y_elems * 4 <= kMaxTiledBytes && (int64_t)pr.CRSpad * pr.Kpad * 4 <= kMaxTiledBytes &&
-                  (!pr.xl || d->c % 8 == 0);  // channels-last gather: whole steps of the smallest bk per tap
+                  pr.y_elems * 4 <= kMaxTiledBytes && (int64_t)pr.CRSpad * pr.Kpad * 4 <= kMaxTiledBytes;
     *out = pr;
     return WPK_OK;
 }
@@ -156,8 +156,6 @@ bool legal_for(const Problem &pr, const wpk_conv_config &cfg)
     if (threads > 1024) return false;                                             // workgroup size
     if (2 * (cfg.bk + 4) * (cfg.bm + cfg.bn) * 4 > kMaxLdsBytes) return false;    // two LDS stages
     if (threads > cfg.bm && (cfg.bk * cfg.bm / threads) % 4 != 0) return false;   // whole k quads per thread
-    // channels-last gather: a step of bk reduction rows lies inside one filter tap
-    if (pr.xl && pr.d.c % cfg.bk != 0) return false;
     int32_t nsteps = (pr.CRS + cfg.bk - 1) / cfg.bk;
     if (cfg.split_k > nsteps) return false;
     // the persistent schedule balances the reduction itself: no fixed slices, no tile remap

@@ -73,9 +73,11 @@ typedef const int __attribute__((address_space(4))) *tap_ptr;
 // LDS row pitch (floats) of a reduction-contiguous tile with BK k values per column.
 __host__ __device__ constexpr int lds_pitch(int bk) { return bk + 4; }
 
-// XL = 0: activations [N][C][H][W], reduction rows ordered (c, r, s) as described above.
-// XL = 1: activations channels-last, [N][H][W][C], reduction rows ordered (r, s, c) and C a
-//   multiple of BK.  A lane still owns one output pixel; four consecutive reduction rows are four
+// XL = 0: reduction rows ordered (c, r, s) and gathered one row at a time as described above, for
+//   activations [N][C][H][W] or (a.xl = 1) channels-last ones: only the window origin and the
+//   strides the host puts into the tap table differ.  This form takes any C.
+// XL = 1 (a.xl = 2): activations channels-last, [N][H][W][C], reduction rows ordered (r, s, c)
+//   and C a multiple of BK.  A lane still owns one output pixel; four consecutive reduction rows are four
 //   consecutive channels of one tap, i.e. 16 contiguous bytes: one buffer_load_dwordx4 per quad.
 //   A step lies inside a single tap (r, s), so one table entry per step gives the tap's byte
 //   offset and mask bits, the channel offset is added on the scalar unit, and there are no
@@ -155,8 +157,8 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
             int n = m / a.PQ, pq = m - n * a.PQ;
             int p = pq / a.Q, q = pq - p * a.Q;
             int ih0 = p * a.stride_h - a.pad_h, iw0 = q * a.stride_w - a.pad_w;
-            xvoff[i] = XL ? ((n * a.H + p * a.stride_h) * a.W + q * a.stride_w) * a.C * 4
-                          : ((n * a.C * a.H + p * a.stride_h) * a.W + q * a.stride_w) * 4;
+            xvoff[i] = a.xl ? ((n * a.H + p * a.stride_h) * a.W + q * a.stride_w) * a.C * 4
+                            : ((n * a.C * a.H + p * a.stride_h) * a.W + q * a.stride_w) * 4;
             unsigned inv = 0x80000000u;
             for (int r = 0; r < a.R; ++r) {
                 int ih = ih0 + r * a.dil_h;
@@ -481,7 +483,40 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                 // is below y_bytes < 2^32
                 const unsigned voff = a.yl ? (unsigned)(((size_t)m * a.K + kbase) * 4)
                                            : (unsigned)((((size_t)n * a.K + kbase) * a.PQ + pq) * 4);
-                if (fused) {
+                if (a.yl == 2 && !atomic) {
+                    // channels-last y with K a multiple of 4 and 16-byte aligned tensors: the four
+                    // registers 4g..4g+3 of a lane are four consecutive channels of its pixel
+                    const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
+                        (void *)(a.bias ? a.bias : a.y), 0, a.bias ? a.K * 4 : 0, 0x00020000);
+                    const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
+                        (void *)(a.res ? a.res : a.y), 0, a.res ? (int)a.y_bytes : 0, 0x00020000);
+                    v4f add[4];
+                    if (fused)
+                        static_for<4>([&](auto G) WPK_LAMBDA {
+                            constexpr int g = decltype(G)::value;
+                            v4f t = __builtin_bit_cast(
+                                v4f, __builtin_amdgcn_raw_buffer_load_b128(brsrc, kbase * 4, 32 * g, 0));
+                            if (kbase + 8 * g < a.K)
+                                t += __builtin_bit_cast(
+                                    v4f, __builtin_amdgcn_raw_buffer_load_b128(rrsrc, voff, 32 * g, 0));
+                            add[g] = t;
+                        });
+                    static_for<4>([&](auto G) WPK_LAMBDA {
+                        constexpr int g = decltype(G)::value;
+                        if (kbase + 8 * g < a.K) {
+                            v4f v = {acc[i * NMT + j][4 * g], acc[i * NMT + j][4 * g + 1],
+                                     acc[i * NMT + j][4 * g + 2], acc[i * NMT + j][4 * g + 3]};
+                            if (fused) {
+                                v += add[g];
+                                if (a.relu)
+                                    v = (v4f){fmaxf(v[0], 0.0f), fmaxf(v[1], 0.0f), fmaxf(v[2], 0.0f),
+                                              fmaxf(v[3], 0.0f)};
+                            }
+                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), yrsrc, voff,
+                                                                   32 * g, 0);
+                        }
+                    });
+                } else if (fused) {
                     const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
                         (void *)(a.bias ? a.bias : a.y), 0, a.bias ? a.K * 4 : 0, 0x00020000);
                     const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -598,7 +633,7 @@ template <int BM, int BN, int BK, int WM, int WN, int PD>
 hipError_t launch_igemm(const IgemmArgs &a, hipStream_t stream)
 {
     dim3 grid((unsigned)(a.persist > 0 ? a.grid_persist : a.tiles_m * a.tiles_n * a.split_k));
-    if (a.xl)
+    if (a.xl == 2)
         hipLaunchKernelGGL((igemm_kernel<BM, BN, BK, WM, WN, PD, 1>), grid, dim3(64 * WM * WN), 0, stream, a);
     else
         hipLaunchKernelGGL((igemm_kernel<BM, BN, BK, WM, WN, PD, 0>), grid, dim3(64 * WM * WN), 0, stream, a);

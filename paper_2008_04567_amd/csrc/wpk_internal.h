@@ -63,6 +63,7 @@ struct Problem {
     int64_t x_elems, w_elems, y_elems;
     bool tiled_ok;   // the tiled family can run it (else only the direct kernel)
     bool xl, yl;     // x / y channels-last (bits 0 and 1 of the descriptor's layout)
+    bool xquad;      // channels-last x gathered as 16-byte channel quads (C a multiple of every K-step)
 };
 int make_problem(const wpk_conv_desc *d, Problem *out);  // WPK_OK or a WPK_E_* code
 std::string desc_key(const wpk_conv_desc *d);
@@ -96,7 +97,10 @@ struct IgemmArgs {
     const float *bias;  // [K] or NULL
     const float *res;   // laid out like y, or NULL
     int32_t relu;       // act = max(., 0) when nonzero
-    int32_t xl, yl;     // 1: x / y (and the residual) are channels-last
+    int32_t xl;         // 0: x is [N][C][H][W]; 1: channels-last, gathered row by row; 2: channels-last,
+                        // gathered as 16-byte channel quads (reduction rows ordered (r, s, c))
+    int32_t yl;         // 1: y (and the residual) are channels-last; 2: also K % 4 == 0 and y, residual and
+                        // bias 16-byte aligned, so a pixel's channel quads move as 16-byte accesses
 };
 
 // What follows the convolution inside the same launch (Section 2.1, operator fusion).

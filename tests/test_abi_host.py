@@ -154,12 +154,10 @@ def test_config_encoding_roundtrip_and_constraint_check():
     assert B.legal_configs(d13(1, 1, 20, 20, 8, 17, 2)) == []                  # > 16 filter rows
     assert B.legal_configs(d13(1, 1, 20, 20, 8, 2, 16)) == []                  # > 15 filter columns
     assert B.legal_configs(d13(1, 1, 20, 20, 8, 16, 15)) != []
-    # channels-last x: a step of bk reduction rows must lie inside one tap, so bk divides C
-    cl = B.make_desc(W.layer("cl", 1, 24, 12, 20, 3, 1, 1), layout=B.NHWC)
-    assert {c.bk for c in B.legal_configs(cl)} == {8}
-    assert B.legal_configs(B.make_desc(W.layer("cl", 1, 20, 12, 20, 3, 1, 1), layout=B.X_NHWC)) == []
-    assert {c.bk for c in B.legal_configs(B.make_desc(W.layer("cl", 1, 20, 12, 20, 3, 1, 1),
-                                                      layout=B.Y_NHWC))} == {8, 16, 32}
+    # channels-last x takes every K-step whatever C is (quads when C % 32 == 0, rows otherwise)
+    for c_in in (3, 20, 24, 64):
+        cl = B.make_desc(W.layer("cl", 1, c_in, 12, 20, 3, 1, 1), layout=B.NHWC)
+        assert {c.bk for c in B.legal_configs(cl, split_k=[1], persist=[0])} == {8, 16, 32}
     with pytest.raises(B.WpkError):
         B.config_from_id(10 ** 9)
     with pytest.raises(B.WpkError):

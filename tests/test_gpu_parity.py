@@ -283,14 +283,21 @@ def test_channels_last_shape_sweep(case):
             PT.check_layout(l, B.NHWC, cfg=c_)
 
 
-def test_channels_last_shapes_outside_the_tiled_gather_use_the_direct_kernel():
-    # 3 input channels (an image): no K-step divides C, so no tiled configuration is legal
-    l = W.layer("cl_rgb", 1, 3, (30, 28), 16, 7, 2, 3, 1, x_dist="u11", w_dist="u11", seed=33)
-    for layout in (B.NHWC, B.X_NHWC):
-        assert B.legal_configs(B.make_desc(l, layout=layout)) == []
-        PT.check_layout(l, layout)
-    assert B.legal_configs(B.make_desc(l, layout=B.Y_NHWC)) != []       # x is NCHW: tiled
-    PT.check_layout(l, B.Y_NHWC)
+def test_channels_last_any_channel_count():
+    """C a multiple of 32 is gathered in 16-byte channel quads; any other C (here an RGB stem and
+    C = 20) row by row through the same kernels; K not a multiple of 4 or an unaligned y takes
+    the scalar stores."""
+    rgb = W.layer("cl_rgb", 1, 3, (30, 28), 16, 7, 2, 3, 1, x_dist="u11", w_dist="u11", seed=33)
+    c20 = W.layer("cl_c20", 2, 20, (13, 11), 18, 3, 1, 1, 1, x_dist="u11", w_dist="u11", seed=34)
+    for l in (rgb, c20):
+        for layout in (B.NHWC, B.X_NHWC, B.Y_NHWC):
+            desc = B.make_desc(l, layout=layout)
+            assert B.legal_configs(desc) != []
+            PT.check_layout(l, layout)
+            for c in (B.make_config(64, 32, 32, 2, 1), B.make_config(128, 64, 16, 2, 2, 3),
+                      B.make_config(64, 64, 8, 2, 1, persist=2)):
+                if B.config_legal(desc, c):
+                    PT.check_layout(l, layout, cfg=c)
 
 
 def test_oversized_filter_uses_the_direct_kernel():
