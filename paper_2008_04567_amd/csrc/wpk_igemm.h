@@ -129,10 +129,10 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     //   kStore  plain stores (the segment is the tile's whole reduction);
     //   kAtomic fp32 atomics into y, which the host zeroed (no workspace given);
     //   kFixup  the tile is shared by fix_n workgroups (reduction slices, or neighbouring runs
-    //           of a persistent launch), this one being number fix_slot: each stores its partial tile to its slot of the workspace and
-    //           bumps the tile's arrival counter; whoever arrives last adds up the other slots
-    //           and stores y.  Nobody waits for anybody, y needs no zeroing, and the counter is
-    //           back at zero when the kernel ends.
+    //           of a persistent launch), this one being number fix_slot: each stores its partial
+    //           tile to its slot of the workspace and bumps the tile's arrival counter; whoever
+    //           arrives last adds up the other slots and stores y.  Nobody waits for anybody, y
+    //           needs no zeroing, and the counter is back at zero when the kernel ends.
     enum { kStore = 0, kAtomic = 1, kFixup = 2 };
     __shared__ int arrival;
     auto run_segment = [&](const int tile, const int kbeg, const int kend, const int mode,

@@ -283,6 +283,25 @@ def test_channels_last_shape_sweep(case):
             PT.check_layout(l, B.NHWC, cfg=c_)
 
 
+def test_channels_last_output_not_16_byte_aligned():
+    """A channels-last y that starts 4 bytes past a 16-byte boundary takes the scalar stores."""
+    torch, dev = PT.torch_dev()
+    l = RAGGED_CL
+    desc = B.make_desc(l, layout=B.NHWC)
+    x, w = W.make_inputs(l)
+    x_cl = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+    y_ref, d_ref = oc.conv2d_layout(oc.shape_from_layer(l), x_cl, w, "NHWC", "NHWC")
+    buf = torch.full((y_ref.size + 9,), 12345.0, device=dev, dtype=torch.float32)
+    yd = buf[1:1 + y_ref.size]
+    assert yd.data_ptr() % 16 == 4
+    B.conv2d_fwd_fused(desc, PT.to_dev(x_cl), PT.to_dev(w), yd, relu=False,
+                       cfg=B.make_config(128, 64, 16, 2, 2, 3))
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    assert host[0] == 12345.0 and np.all(host[1 + y_ref.size:] == 12345.0)
+    PT.assert_close(host[1:1 + y_ref.size], y_ref, d_ref, "unaligned channels-last y")
+
+
 def test_channels_last_any_channel_count():
     """C a multiple of 32 is gathered in 16-byte channel quads; any other C (here an RGB stem and
     C = 20) row by row through the same kernels; K not a multiple of 4 or an unaligned y takes
