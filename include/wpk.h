@@ -12,15 +12,17 @@
  *
  * Conventions for every entry point
  *   - x, w, y are DEVICE pointers owned by the caller: dense fp32, x = [N][C][H][W],
- *     w = [K][C][R][S], y = [N][K][P][Q], at least 4-byte aligned.  y is overwritten in full
- *     (no accumulate, no bias).  x and y must not overlap.
+ *     w = [K][C][R][S], y = [N][K][P][Q] (x and/or y channels-last instead when the descriptor's
+ *     layout says so), at least 4-byte aligned.  y is overwritten in full (no accumulate).  x
+ *     and y must not overlap.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued
  *     on it and the call returns without synchronising, unless stated otherwise.
  *   - Descriptors and config structs are HOST memory, copied by value during the call.
  *   - Return value: 0 (WPK_OK) or a negative WPK_E_* code; functions that return an id return
  *     it as a non-negative int.  Nothing throws or aborts across this boundary.
  *   - Calls that share a stream are ordered; calls on different streams that use the one-shot
- *     entry points share library scratch (packed weights, lookup tables) and must not overlap.
+ *     entry points share library scratch (packed weights, lookup tables, the workspace in which
+ *     workgroups that share an output tile meet) and must not overlap.
  *     Plans own their scratch and may run concurrently with each other; the layers of one plan
  *     share it and must run one after another (one stream, or ordered streams).
  *   - The library never falls back to the CPU: without a usable GPU every compute entry point
