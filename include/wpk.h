@@ -276,6 +276,13 @@ void wpk_plan_destroy(wpk_plan *plan);
  * 0 turns the workspace off.  Applies to launches prepared afterwards; WPK_E_BAD_ARG if negative. */
 int wpk_set_workspace_limit(int64_t bytes);
 
+/* Workspace a launch of `cfg` on a device with `compute_units` CUs uses to sum shared tiles: the
+ * byte count (0: nothing is shared, atomics were asked for, or the cap is exceeded), and through
+ * the optional pointers the number of shared tiles and of partial-tile slots per shared tile.
+ * Host only; negative WPK_E_* on a bad descriptor or an illegal configuration. */
+int64_t wpk_config_workspace_bytes(const wpk_conv_desc *d, const wpk_conv_config *cfg,
+                                   int32_t compute_units, int64_t *shared_tiles, int64_t *slots);
+
 /* ---- introspection used by the benchmark ----------------------------------------------------- */
 /* Name of the device kernel a config launches (static storage), e.g. "wpk_igemm_128x64x16_2x2_p2". */
 const char *wpk_config_kernel_name(const wpk_conv_config *cfg);

@@ -135,6 +135,8 @@ def lib():
             "wpk_device_info": (I, [ctypes.c_char_p, ctypes.c_int32, i32p]),
             "wpk_version": (ctypes.c_char_p, []),
             "wpk_set_workspace_limit": (I, [ctypes.c_int64]),
+            "wpk_config_workspace_bytes": (ctypes.c_int64, [P(ConvDesc), P(ConvConfig), ctypes.c_int32,
+                                                            P(ctypes.c_int64), P(ctypes.c_int64)]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -445,6 +447,16 @@ class Plan:
             self.destroy()
         except Exception:
             pass
+
+
+def config_workspace(desc, cfg, compute_units=256):
+    """(bytes, shared tiles, slots per shared tile) of the workspace a launch of cfg uses."""
+    tiles, slots = ctypes.c_int64(), ctypes.c_int64()
+    nbytes = lib().wpk_config_workspace_bytes(ctypes.byref(desc), ctypes.byref(cfg), compute_units,
+                                              ctypes.byref(tiles), ctypes.byref(slots))
+    if nbytes < 0:
+        raise WpkError(int(nbytes), "wpk_config_workspace_bytes")
+    return int(nbytes), tiles.value, slots.value
 
 
 def set_workspace_limit(nbytes):

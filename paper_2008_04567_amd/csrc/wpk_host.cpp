@@ -540,6 +540,20 @@ int wpk_cache_load(const char *path)
 }
 
 // ---- tuning options and the engine ---------------------------------------------------------------
+int64_t wpk_config_workspace_bytes(const wpk_conv_desc *d, const wpk_conv_config *cfg,
+                                   int32_t compute_units, int64_t *shared_tiles, int64_t *slots)
+{
+    if (!cfg) return WPK_E_NULL_PTR;
+    Problem pr;
+    int rc = make_problem(d, &pr);
+    if (rc != WPK_OK) return rc;
+    if (!legal_for(pr, *cfg)) return WPK_E_NO_CONFIG;
+    FixupNeed n = fixup_need(pr, *cfg, compute_units);
+    if (shared_tiles) *shared_tiles = n.shared_tiles;
+    if (slots) *slots = n.maxc;
+    return n.bytes;
+}
+
 int wpk_set_workspace_limit(int64_t bytes)
 {
     if (bytes < 0) return WPK_E_BAD_ARG;

@@ -5,6 +5,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from oracle import conv as oc
@@ -255,3 +256,53 @@ def test_workspace_limit_argument_check():
     L = B.lib()
     assert L.wpk_set_workspace_limit(-1) == B.E_BAD_ARG
     assert L.wpk_set_workspace_limit(1 << 30) == 0
+
+
+def test_workspace_slots_cover_every_sharer_of_a_tile():
+    """The kernel indexes a shared tile's slots by the position of a workgroup among the tile's
+    sharers.  Re-derive the sharers from the schedule's definition (persistent: the steps of the
+    tiles beyond the last whole round, laid end to end and cut into G runs of q or q+1; split:
+    the non-empty slices) and check that the slot count the host reserves is never too small."""
+    rng = np.random.default_rng(5)
+    checked = 0
+    for _ in range(300):
+        n, c, hw, k = int(rng.integers(1, 9)), int(rng.integers(1, 200)), int(rng.integers(3, 40)), int(rng.integers(1, 300))
+        rs = int(rng.choice([1, 3, 5]))
+        d = B.make_desc(W.layer("w", n, c, hw, k, rs, 1, rs // 2))
+        P, Q = B.conv_out_shape(d)
+        cus = int(rng.choice([8, 64, 256, 304]))
+        for cfg in (B.make_config(64, 32, 8, 2, 1, persist=int(rng.integers(1, 5))),
+                    B.make_config(128, 64, 16, 2, 2, persist=int(rng.integers(1, 5))),
+                    B.make_config(64, 64, 32, 2, 2, split_k=int(rng.choice([2, 3, 5, 7, 11, 16, 24])))):
+            if not B.config_legal(d, cfg):
+                continue
+            nbytes, shared, slots = B.config_workspace(d, cfg, cus)
+            tiles = -(-n * P * Q // cfg.bm) * -(-k // cfg.bn)
+            nsteps = -(-c * rs * rs // cfg.bk)
+            if cfg.persist == 0:
+                per = -(-nsteps // cfg.split_k)
+                want_shared, want_slots = tiles, -(-nsteps // per)
+                if want_slots <= 1:
+                    want_shared = want_slots = 0
+            else:
+                G = cfg.persist * cus
+                rest = tiles - tiles // G * G
+                units = rest * nsteps
+                q, rem = divmod(units, G)
+                start = lambda g: g * q + min(g, rem)
+                owners = [0] * rest
+                for g in range(G):            # every run marks the tiles it touches
+                    u0, u1 = start(g), start(g + 1)
+                    if u1 > u0:
+                        for j in range(u0 // nsteps, (u1 - 1) // nsteps + 1):
+                            owners[j] += 1
+                want_shared = rest if rest and nsteps > 1 else 0
+                want_slots = max(owners) if want_shared else 0
+            if nbytes == 0:
+                assert want_shared == 0 or want_slots <= 1 or shared == 0
+                continue
+            assert shared == want_shared
+            assert slots >= want_slots, (cfg, cus, tiles, nsteps, slots, want_slots)
+            assert nbytes == (1 << 20) + shared * slots * cfg.bm * cfg.bn * 4
+            checked += 1
+    assert checked > 100
