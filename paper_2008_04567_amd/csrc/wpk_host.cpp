@@ -205,13 +205,41 @@ FixupNeed fixup_need(const Problem &pr, const wpk_conv_config &cfg, int compute_
     return n;
 }
 
-// Untuned default: smallest estimated time under a crude model -- workgroups are dealt to the
-// compute units in rounds, a workgroup costs its multiply-accumulate count plus a fixed
-// per-step and per-workgroup overhead, small wave tiles pay for their operand re-reads and a
-// split reduction pays for its extra passes over y.
+// Untuned default, distilled from exhaustive searches over the layer shapes of the workloads:
+// 32x32 wave tiles in 64-pixel workgroup tiles with the largest K-step win or come within a few
+// percent nearly everywhere, provided the launch has 3-4 workgroups per compute unit; where the
+// tiles alone do not give that many, the reduction is split, and many small slices add up with
+// atomics rather than through the workspace.  Falls back to a crude cost model over all
+// variants if that choice is illegal for the shape.
+static void model_config(const Problem &pr, int compute_units, wpk_conv_config *out);
 void default_config(const Problem &pr, int compute_units, wpk_conv_config *out)
 {
     if (compute_units <= 0) compute_units = 256;
+    wpk_conv_config c = {64, pr.d.k <= 32 ? 32 : 64, pr.CRS >= 64 ? 32 : pr.CRS >= 32 ? 16 : 8, 2,
+                         pr.d.k <= 32 ? 1 : 2, 1, 1, 0, 2, 0};
+    int64_t tiles = ((pr.M + c.bm - 1) / c.bm) * ((pr.d.k + c.bn - 1) / c.bn);
+    int64_t nsteps = (pr.CRS + c.bk - 1) / c.bk;
+    // slices of at least four steps, enough of them for 3.5 workgroups per compute unit
+    int64_t want = std::min<int64_t>((7 * (int64_t)compute_units / 2 + tiles / 2) / tiles, nsteps / 4);
+    for (int i = 0; i < kGeneCounts[5]; ++i)
+        if (kSplitVals[i] <= want) c.split_k = kSplitVals[i];
+    // atomics where many slices meet in a small output (zeroing it is cheap and the last
+    // workgroup need not read every slot); the workspace otherwise
+    int64_t per = (nsteps + c.split_k - 1) / c.split_k, slices = (nsteps + per - 1) / per;
+    c.reduce = (slices >= 5 && pr.y_elems * 4 <= (1 << 20)) || slices > 12 ? 1 : 0;
+    if (legal_for(pr, c)) {
+        *out = c;
+        return;
+    }
+    model_config(pr, compute_units, out);
+}
+
+// Smallest estimated time under a crude model -- workgroups are dealt to the compute units in
+// rounds, a workgroup costs its multiply-accumulate count plus a fixed per-step and
+// per-workgroup overhead, small wave tiles pay for their operand re-reads and a split reduction
+// pays for its extra passes over y.
+static void model_config(const Problem &pr, int compute_units, wpk_conv_config *out)
+{
     double best = 1e300;
     wpk_conv_config bc = {128, 64, 16, 2, 2, 1, 1, 0, 2, 0};
     for (int i = 0; i < kNumVariants; ++i) {
@@ -236,8 +264,6 @@ void default_config(const Problem &pr, int compute_units, wpk_conv_config *out)
             if (cost < best) { best = cost; bc = c; }
         }
     }
-    // many small slices: summing their slots one after another costs the last workgroup more
-    // than atomics and a zeroing launch do
     int64_t nsteps = (pr.CRS + bc.bk - 1) / bc.bk, per = (nsteps + bc.split_k - 1) / bc.split_k;
     bc.reduce = (nsteps + per - 1) / per > 8 ? 1 : 0;
     *out = bc;
