@@ -102,6 +102,9 @@ def main():
     ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc", "x_nhwc", "y_nhwc"],
                     help="activation layout: channels-last x and y, or one of the two mixed forms "
                          "(the convolution then also transforms the layout)")
+    ap.add_argument("--pipeline", type=int, default=1, choices=[1, 2],
+                    help="2: run the timed passes as two half-batch chains on two streams "
+                         "(wpk_plan_set_pipeline); the per-layer event loop stays unsplit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device copy (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -153,6 +156,18 @@ def main():
                                          rep.evaluations, rep.generations, rep.seconds))
         if args.cache:
             B.cache_save(args.cache)
+    if args.pipeline == 2 and not args.no_tune:     # the half-batch shapes get their own search
+        for l in layers:
+            for nh in {(l["n"] + 1) // 2, l["n"] // 2}:
+                dh = B.make_desc(dict(l, n=nh), layout=layout)
+                if B.cache_lookup(dh) is None:
+                    try:
+                        B.conv_tune_ex(dh, opt, force=False)
+                    except B.WpkError as e:
+                        if e.status != B.E_UNSUPPORTED:
+                            raise
+        if args.cache:
+            B.cache_save(args.cache)
     t_tune = time.perf_counter() - t_tune
 
     epi = set(t for t in args.fused.split(",") if t)
@@ -193,6 +208,8 @@ def main():
         else:
             plan.run(xa, ya, stream)
 
+    if args.pipeline == 2:
+        plan.set_pipeline(2)
     for s_ in range(args.warmup):
         one_pass(s_)
     torch.cuda.synchronize()
@@ -207,6 +224,7 @@ def main():
     total_flops = float(sum(flops))
     value = total_flops / (ms_per_step * 1e-3) / 1e12
 
+    plan.set_pipeline(1)
     # ---- per-layer durations with events on the launch stream (same steps count) -------------
     n = len(layers)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(n + 1)] for _ in range(args.steps)]
@@ -262,7 +280,9 @@ def main():
                       "activations": "rotated through %d copies (read from HBM)" % copies if args.cold
                                      else "one set, resident in the memory-side cache between passes",
                       "epilogue": "fused: " + "+".join(sorted(epi)) if epi else "none",
-                      "layout": args.layout},
+                      "layout": args.layout,
+                      "schedule": "two half-batch chains on two streams" if args.pipeline == 2
+                                  else "one launch per layer on one stream"},
            "pct_fp32_mfma_peak": round(100 * value / FP32_MFMA_PEAK_TFLOPS, 2),
            "roofline": roofline, "layers": rows}
     if args.calibrate_copy:

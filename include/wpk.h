@@ -251,6 +251,18 @@ int wpk_plan_run(wpk_plan *plan, const float *const *x, float *const *y, void *s
 /* Run one layer of the plan. */
 int wpk_plan_run_layer(wpk_plan *plan, int32_t layer, const float *x, float *y, void *stream);
 
+/* Two-way pipelining (ways = 2; 1 turns it off): every layer's batch is cut into two halves that
+ * run as two independent chains, the first on the caller's stream and the second on a stream the
+ * plan owns, forked from and joined to the caller's stream once per wpk_plan_run(_fused) call (once
+ * per layer for the run_layer calls).  Convolution treats the images of a batch independently,
+ * so the results are those of the unsplit plan whatever the layers feed each other; what it buys
+ * is that the ramp, the meeting of shared tiles and the drain of one chain's launches hide
+ * behind the other chain's arithmetic (about 6 % on a 53-layer stack at N = 16; it does not pay
+ * for passes of a few layers).  Each half uses the cached configuration of its own descriptor
+ * (batch n/2) if there is one, else the default.  WPK_E_UNSUPPORTED if a layer has batch 1.
+ * Synchronises the device. */
+int wpk_plan_set_pipeline(wpk_plan *plan, int32_t ways);
+
 /* Give layer `layer` a fused epilogue (see wpk_conv2d_fwd_fused): `bias` is a DEVICE pointer to K
  * floats, copied into the plan on `stream` (NULL: no bias); relu != 0 adds the rectifier.  Every
  * later run of the layer, fused or not, applies it. */

@@ -126,6 +126,7 @@ def lib():
             "wpk_plan_set_epilogue": (I, [V, ctypes.c_int32, V, ctypes.c_int32, V]),
             "wpk_plan_run_layer_fused": (I, [V, ctypes.c_int32, V, V, V, V]),
             "wpk_plan_run_fused": (I, [V, P(V), P(V), P(V), V]),
+            "wpk_plan_set_pipeline": (I, [V, ctypes.c_int32]),
             "wpk_plan_num_layers": (I, [V]),
             "wpk_plan_num_unique": (I, [V]),
             "wpk_plan_layer_config": (I, [V, ctypes.c_int32, P(ConvConfig)]),
@@ -420,6 +421,9 @@ class Plan:
 
     def run_fused(self, xa, ra, ya, stream=None):
         _check(lib().wpk_plan_run_fused(self.handle, xa, ra, ya, _stream(stream)), "wpk_plan_run_fused")
+
+    def set_pipeline(self, ways):
+        _check(lib().wpk_plan_set_pipeline(self.handle, int(ways)), "wpk_plan_set_pipeline")
 
     def num_layers(self):
         return lib().wpk_plan_num_layers(self.handle)

@@ -648,8 +648,17 @@ struct wpk_plan {
         float *bias;  // library-owned copy of the layer's bias, or NULL
         int relu;
         bool direct;  // outside the tiled family: wp holds plain [K][C][R][S] weights for the direct kernel
+        // two-way pipelining: the batch split into images [0, half[0].d.n) and the rest
+        Problem half[2];
+        wpk_conv_config half_cfg[2];
     };
     FixupBuf fix;  // fix-up workspace shared by the layers (they run one after another)
+    // two-way pipelining (wpk_plan_set_pipeline): the second half-batch chain runs on `side`
+    // with a workspace of its own; fork/join order it against the caller's stream
+    int ways = 1;
+    hipStream_t side = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    FixupBuf fix_side;
     std::vector<Layer> layers;
     std::vector<int32_t *> ktabs;  // one per distinct descriptor
 };
@@ -999,6 +1008,41 @@ int wpk_plan_set_epilogue(wpk_plan *plan, int32_t layer, const float *bias, int3
     return WPK_OK;
 }
 
+// One layer (or, with which = 0/1, one half-batch of it) on stream st.
+static int plan_launch(wpk_plan *plan, wpk_plan::Layer &L, int which, const float *x,
+                       const float *residual, float *y, hipStream_t st)
+{
+    const Problem &pr = which < 0 ? L.pr : L.half[which];
+    const wpk_conv_config &cfg = which < 0 ? L.cfg : L.half_cfg[which];
+    if (which == 1) {  // the second half starts after the images of the first
+        x += L.half[0].x_elems;
+        y += L.half[0].y_elems;
+        if (residual) residual += L.half[0].y_elems;
+    }
+    Epilogue epi;
+    epi.bias = L.bias; epi.res = residual; epi.relu = L.relu;
+    if (L.direct) {
+        int rc = run_ref(pr, x, L.wp, y, nullptr, st);
+        return rc != WPK_OK ? rc : run_epilogue(pr, epi, y, st);
+    }
+    return run_config(pr, cfg, plan->ktabs[L.unique], x, L.wp, y, which == 1 ? &plan->fix_side : &plan->fix,
+                      st, epi);
+}
+
+static int plan_fork(wpk_plan *plan, hipStream_t user)
+{
+    WPK_HIP(hipEventRecord(plan->fork, user));
+    WPK_HIP(hipStreamWaitEvent(plan->side, plan->fork, 0));
+    return WPK_OK;
+}
+
+static int plan_join(wpk_plan *plan, hipStream_t user)
+{
+    WPK_HIP(hipEventRecord(plan->join, plan->side));
+    WPK_HIP(hipStreamWaitEvent(user, plan->join, 0));
+    return WPK_OK;
+}
+
 int wpk_plan_run_layer_fused(wpk_plan *plan, int32_t layer, const float *x, const float *residual,
                              float *y, void *stream)
 {
@@ -1006,14 +1050,48 @@ int wpk_plan_run_layer_fused(wpk_plan *plan, int32_t layer, const float *x, cons
     if (layer < 0 || layer >= (int)plan->layers.size()) return WPK_E_BAD_ARG;
     wpk_plan::Layer &L = plan->layers[layer];
     if (!L.has_w) return WPK_E_BAD_ARG;
-    Epilogue epi;
-    epi.bias = L.bias; epi.res = residual; epi.relu = L.relu;
-    if (L.direct) {
-        int rc = run_ref(L.pr, x, L.wp, y, nullptr, (hipStream_t)stream);
-        return rc != WPK_OK ? rc : run_epilogue(L.pr, epi, y, (hipStream_t)stream);
+    if (plan->ways == 1) return plan_launch(plan, L, -1, x, residual, y, (hipStream_t)stream);
+    int rc = plan_fork(plan, (hipStream_t)stream);
+    if (rc == WPK_OK) rc = plan_launch(plan, L, 0, x, residual, y, (hipStream_t)stream);
+    if (rc == WPK_OK) rc = plan_launch(plan, L, 1, x, residual, y, plan->side);
+    int rj = plan_join(plan, (hipStream_t)stream);  // joined even after a failed launch
+    return rc != WPK_OK ? rc : rj;
+}
+
+int wpk_plan_set_pipeline(wpk_plan *plan, int32_t ways)
+{
+    if (!plan) return WPK_E_NULL_PTR;
+    if (ways != 1 && ways != 2) return WPK_E_BAD_ARG;
+    if (ways == 1) {
+        plan->ways = 1;
+        return WPK_OK;
     }
-    return run_config(L.pr, L.cfg, plan->ktabs[L.unique], x, L.wp, y, &plan->fix, (hipStream_t)stream,
-                      epi);
+    for (auto &L : plan->layers)
+        if (L.pr.d.n < 2) return WPK_E_UNSUPPORTED;
+    if (!plan->side) {
+        WPK_HIP(hipStreamCreateWithFlags(&plan->side, hipStreamNonBlocking));
+        WPK_HIP(hipEventCreateWithFlags(&plan->fork, hipEventDisableTiming));
+        WPK_HIP(hipEventCreateWithFlags(&plan->join, hipEventDisableTiming));
+    }
+    WPK_HIP(hipDeviceSynchronize());  // workspaces may grow below
+    for (auto &L : plan->layers) {
+        for (int h = 0; h < 2; ++h) {
+            wpk_conv_desc d = L.pr.d;
+            d.n = h == 0 ? (L.pr.d.n + 1) / 2 : L.pr.d.n / 2;
+            int rc = make_problem(&d, &L.half[h]);
+            if (rc != WPK_OK) return rc;
+            if (L.direct) continue;
+            if (wpk_cache_lookup(&d, &L.half_cfg[h]) != 1 || !legal_for(L.half[h], L.half_cfg[h]))
+                default_config(L.half[h], g_cus, &L.half_cfg[h]);
+            FixupNeed need = fixup_need(L.half[h], L.half_cfg[h], g_cus);
+            if (need.bytes > 0) {
+                rc = fixup_reserve(h == 0 ? plan->fix : plan->fix_side, (size_t)need.bytes);
+                if (rc != WPK_OK) return rc;
+            }
+        }
+    }
+    plan->ways = 2;
+    return WPK_OK;
 }
 
 int wpk_plan_run_layer(wpk_plan *plan, int32_t layer, const float *x, float *y, void *stream)
@@ -1025,12 +1103,27 @@ int wpk_plan_run_fused(wpk_plan *plan, const float *const *x, const float *const
                        float *const *y, void *stream)
 {
     if (!plan || !x || !y) return WPK_E_NULL_PTR;
-    for (size_t i = 0; i < plan->layers.size(); ++i) {
-        int rc = wpk_plan_run_layer_fused(plan, (int32_t)i, x[i], residual ? residual[i] : nullptr,
-                                          y[i], stream);
-        if (rc != WPK_OK) return rc;
+    if (plan->ways == 1) {
+        for (size_t i = 0; i < plan->layers.size(); ++i) {
+            int rc = wpk_plan_run_layer_fused(plan, (int32_t)i, x[i], residual ? residual[i] : nullptr,
+                                              y[i], stream);
+            if (rc != WPK_OK) return rc;
+        }
+        return WPK_OK;
     }
-    return WPK_OK;
+    // two chains of half-batches: one on the caller's stream, one on the plan's, forked and
+    // joined once around the whole pass
+    for (size_t i = 0; i < plan->layers.size(); ++i)
+        if (!x[i] || !y[i]) return WPK_E_NULL_PTR;
+        else if (!plan->layers[i].has_w) return WPK_E_BAD_ARG;
+    int rc = plan_fork(plan, (hipStream_t)stream);
+    for (size_t i = 0; i < plan->layers.size() && rc == WPK_OK; ++i) {
+        const float *r = residual ? residual[i] : nullptr;
+        rc = plan_launch(plan, plan->layers[i], 0, x[i], r, y[i], (hipStream_t)stream);
+        if (rc == WPK_OK) rc = plan_launch(plan, plan->layers[i], 1, x[i], r, y[i], plan->side);
+    }
+    int rj = plan_join(plan, (hipStream_t)stream);  // joined even after a failed launch
+    return rc != WPK_OK ? rc : rj;
 }
 
 int wpk_plan_run(wpk_plan *plan, const float *const *x, float *const *y, void *stream)
@@ -1074,6 +1167,10 @@ void wpk_plan_destroy(wpk_plan *plan)
     for (int32_t *t : plan->ktabs)
         if (t) (void)hipFree(t);
     fixup_release(plan->fix);
+    fixup_release(plan->fix_side);
+    if (plan->fork) (void)hipEventDestroy(plan->fork);
+    if (plan->join) (void)hipEventDestroy(plan->join);
+    if (plan->side) (void)hipStreamDestroy(plan->side);
     delete plan;
 }
 

@@ -153,3 +153,66 @@ def test_plan_fused_basic_block():
     r2p, d2p, _ = oc.conv2d(oc.shape_from_layer(lb), y1h, w2)
     PT.assert_close(y2.cpu().numpy(), r2p, d2p, "block layer 2 plain")
     plan.destroy()
+
+
+def test_plan_two_way_pipelining_of_a_dependent_chain():
+    """Three layers feeding each other (the second with a residual from the chain's input), batch 5,
+    run as two half-batch chains on two streams: identical to the unsplit plan to the last bit
+    for plainly stored outputs is not required (split layers sum in arrival order), so both are
+    held to the oracle bound, layer by layer with the GPU's own inputs."""
+    from oracle import conv as oc
+    torch, dev = PT.torch_dev()
+    n = 5
+    la = W.layer("pipe.a", n, 16, (15, 13), 32, 3, 1, 1, x_dist="u11", seed=71)
+    lb = W.layer("pipe.b", n, 32, (15, 13), 32, 3, 1, 1, x_dist="u11", seed=72)
+    lc = W.layer("pipe.c", n, 32, (15, 13), 24, 1, 1, 0, x_dist="u11", seed=73)
+    layers = [la, lb, lc]
+    plan = B.Plan([B.make_desc(l) for l in layers])
+    plan.set_layer_config(1, B.make_config(64, 32, 16, 2, 1, 4))
+    x0, _ = W.make_inputs(la)
+    ws = [W.make_inputs(l)[1] for l in layers]
+    rng = np.random.default_rng(2)
+    res_b = rng.uniform(-1, 1, (n, 32, 15, 13)).astype(np.float32)
+    xd = PT.to_dev(x0)
+    ya = torch.empty((n, 32, 15, 13), device=dev)
+    yb = torch.empty((n, 32, 15, 13), device=dev)
+    yc = torch.empty((n, 24, 15, 13), device=dev)
+    for i, w in enumerate(ws):
+        plan.set_weights(i, PT.to_dev(w))
+    plan.set_epilogue(0, None, relu=True)
+    plan.set_epilogue(1, None, relu=True)
+    xa, yarr = plan.pointer_arrays([xd, ya, yb], [ya, yb, yc])
+    ra = plan.residual_array([None, PT.to_dev(res_b), None])
+
+    def check(tag):
+        torch.cuda.synchronize()
+        ha, hb, hc = ya.cpu().numpy(), yb.cpu().numpy(), yc.cpu().numpy()
+        r, d = oc.conv2d_fused(oc.shape_from_layer(la), x0, ws[0], relu=True)
+        PT.assert_close(ha, r, d, tag + " layer a")
+        r, d = oc.conv2d_fused(oc.shape_from_layer(lb), ha, ws[1], residual=res_b, relu=True)
+        PT.assert_close(hb, r, d, tag + " layer b")
+        r, d, _ = oc.conv2d(oc.shape_from_layer(lc), hb, ws[2])
+        PT.assert_close(hc, r, d, tag + " layer c")
+
+    plan.run_fused(xa, ra, yarr)
+    check("one chain")
+    for t in (ya, yb, yc):
+        t.fill_(777.0)
+    plan.set_pipeline(2)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):               # a caller's stream other than the default one
+        for _ in range(3):
+            plan.run_fused(xa, ra, yarr, side)
+    side.synchronize()
+    check("two chains")
+    yc.fill_(777.0)
+    plan.run_layer(2, yb, yc)                   # a single layer forks and joins by itself
+    check("two chains, single layer")
+    plan.set_pipeline(1)
+    plan.run_fused(xa, ra, yarr)
+    check("back to one chain")
+    one = B.Plan([B.make_desc(W.layer("n1", 1, 8, 8, 8, 3, 1, 1))])
+    with pytest.raises(B.WpkError):
+        one.set_pipeline(2)                     # nothing to split at batch 1
+    one.destroy()
+    plan.destroy()
