@@ -216,3 +216,53 @@ def test_plan_two_way_pipelining_of_a_dependent_chain():
         one.set_pipeline(2)                     # nothing to split at batch 1
     one.destroy()
     plan.destroy()
+
+
+@pytest.mark.parametrize("ways", [1, 2])
+def test_plan_run_can_be_captured_in_a_hip_graph(ways):
+    """A plan's pass only launches kernels (zeroing before atomics is a fill kernel, the workspace
+    counters reset themselves), so it can be captured once and replayed.  Replayed several times
+    with eager passes and synchronisations in between; every replay must give the eager result
+    (split layers sum in arrival order, hence the oracle bound rather than bit equality)."""
+    from oracle import conv as oc
+    torch, dev = PT.torch_dev()
+    layers = [W.layer("g.a", 4, 16, (14, 12), 40, 3, 1, 1, x_dist="u11", seed=81),
+              W.layer("g.b", 4, 40, (14, 12), 24, 3, 1, 1, x_dist="u11", seed=82),
+              W.layer("g.c", 4, 24, (14, 12), 16, 1, 1, 0, x_dist="u11", seed=83)]
+    plan = B.Plan([B.make_desc(l) for l in layers])
+    plan.set_layer_config(0, B.make_config(64, 32, 16, 2, 1, 3))              # workspace
+    plan.set_layer_config(1, B.make_config(64, 64, 8, 2, 1, 5, reduce=1))     # zero fill + atomics
+    plan.set_layer_config(2, B.make_config(64, 32, 8, 2, 1, persist=2))       # persistent
+    plan.set_pipeline(ways)
+    x0, _ = W.make_inputs(layers[0])
+    ws = [W.make_inputs(l)[1] for l in layers]
+    for i, w in enumerate(ws):
+        plan.set_weights(i, PT.to_dev(w))
+    xd = PT.to_dev(x0)
+    ys = [torch.empty((4, l["k"], 14, 12), device=dev) for l in layers]
+    xa, ya = plan.pointer_arrays([xd, ys[0], ys[1]], ys)
+
+    def check(tag):
+        torch.cuda.synchronize()
+        h = [y.cpu().numpy() for y in ys]
+        ins = [x0, h[0], h[1]]
+        for i, l in enumerate(layers):
+            r, d, _ = oc.conv2d(oc.shape_from_layer(l), ins[i], ws[i])
+            PT.assert_close(h[i], r, d, "%s layer %d" % (tag, i))
+
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        plan.run(xa, ya, s)
+        check("eager")
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            plan.run(xa, ya, s)
+        for rep in range(3):
+            for y in ys:
+                y.fill_(float("nan"))
+            g.replay()
+            check("replay %d" % rep)
+            plan.run(xa, ya, s)                      # eager work between the replays
+            check("eager after replay %d" % rep)
+    del g
+    plan.destroy()
