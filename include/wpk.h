@@ -243,6 +243,8 @@ int wpk_conv_plan(const wpk_conv_desc *layers, int32_t n_layers, int32_t tune, w
 /* Copy and re-pack layer `layer`'s weights (device pointer, KCRS) into the plan, on `stream`. */
 int wpk_plan_set_weights(wpk_plan *plan, int32_t layer, const float *w, void *stream);
 
+/* The run calls below only enqueue kernel launches (and, with pipelining, event records and
+ * waits): they allocate nothing and may be recorded by a stream capture into a HIP graph. */
 /* Run every layer in order on `stream`: y[i] = conv(x[i], weights of layer i).  x and y are HOST
  * arrays of n_layers DEVICE pointers.  Weights of every layer must have been set.  A layer with
  * an epilogue (wpk_plan_set_epilogue) applies it. */
