@@ -375,6 +375,20 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     a.y_bytes = (uint32_t)(pr.y_elems * 4);
     a.persist = cfg.persist;
     a.grid_persist = cfg.persist * (g_cus > 0 ? g_cus : 256);
+    a.tiles = a.tiles_m * a.tiles_n;
+    a.tiles_dp = cfg.persist > 0 ? a.tiles / a.grid_persist * a.grid_persist : 0;
+    {
+        int64_t units = (int64_t)(a.tiles - a.tiles_dp) * a.nsteps;  // < 2^31: checked by legal_for
+        a.sk_q = cfg.persist > 0 ? (int32_t)(units / a.grid_persist) : 0;
+        a.sk_rem = cfg.persist > 0 ? (int32_t)(units % a.grid_persist) : 0;
+    }
+    a.div_pq = make_fastdiv((uint32_t)a.PQ);
+    a.div_q = make_fastdiv((uint32_t)a.Q);
+    a.div_tiles_n = make_fastdiv((uint32_t)a.tiles_n);
+    a.div_tiles = make_fastdiv((uint32_t)a.tiles);
+    a.div_nsteps = make_fastdiv((uint32_t)a.nsteps);
+    a.div_q1 = make_fastdiv((uint32_t)a.sk_q + 1);
+    a.div_q0 = make_fastdiv((uint32_t)std::max(a.sk_q, 1));
     a.ws = nullptr;
     a.ws_cnt = nullptr;
     a.ws_maxc = 0;

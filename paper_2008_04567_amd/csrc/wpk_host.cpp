@@ -164,6 +164,8 @@ bool legal_for(const Problem &pr, const wpk_conv_config &cfg)
     if (cfg.reduce != 0 && cfg.split_k == 1 && cfg.persist == 0) return false;
     int64_t tiles = ((pr.M + cfg.bm - 1) / cfg.bm) * ((pr.d.k + cfg.bn - 1) / cfg.bn);
     if (tiles * cfg.split_k > 0x7fffffff) return false;
+    // the persistent schedule counts reduction steps of up to 4*CUs tiles in 32 bits
+    if (cfg.persist > 0 && (int64_t)nsteps * 4096 > 0x7fffffff) return false;
     return true;
 }
 

@@ -67,6 +67,11 @@ __device__ __forceinline__ void static_for(F &&f)
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
+__device__ __forceinline__ int fdiv(int n, const FastDiv &f)
+{
+    return f.d == 1 ? n : (int)(__umulhi((unsigned)n, f.mul) >> f.sh);
+}
+
 // The tap table is read through the constant address space: wave-uniform scalar loads.
 typedef const int __attribute__((address_space(4))) *tap_ptr;
 
@@ -138,7 +143,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     auto run_segment = [&](const int tile, const int kbeg, const int kend, const int mode,
                            const int fix_j, const int fix_slot, const int fix_n) WPK_LAMBDA {
     if (kbeg >= kend) return;  // nothing to reduce: touch neither the tap table nor y
-    const int tile_n = tile % a.tiles_n, tile_m = tile / a.tiles_n;
+    const int tile_m = fdiv(tile, a.div_tiles_n), tile_n = tile - tile_m * a.tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     // ---- per-thread gather state ---------------------------------------------------------------
@@ -154,8 +159,8 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
         xvoff[i] = 0;
         xinv[i] = 0xffffffffu;
         if (m < a.M) {
-            int n = m / a.PQ, pq = m - n * a.PQ;
-            int p = pq / a.Q, q = pq - p * a.Q;
+            int n = fdiv(m, a.div_pq), pq = m - n * a.PQ;
+            int p = fdiv(pq, a.div_q), q = pq - p * a.Q;
             int ih0 = p * a.stride_h - a.pad_h, iw0 = q * a.stride_w - a.pad_w;
             xvoff[i] = a.xl ? ((n * a.H + p * a.stride_h) * a.W + q * a.stride_w) * a.C * 4
                             : ((n * a.C * a.H + p * a.stride_h) * a.W + q * a.stride_w) * 4;
@@ -475,7 +480,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
         constexpr int j = decltype(J)::value;
         int m = m0 + wave_m * TM + j * 32 + lcol;
         if (m < a.M) {
-            int n = m / a.PQ, pq = m - n * a.PQ;
+            int n = fdiv(m, a.div_pq), pq = m - n * a.PQ;
             static_for<NNT>([&](auto I) WPK_LAMBDA {
                 constexpr int i = decltype(I)::value;
                 const int kbase = n0 + wave_n * TN + i * 32 + 4 * lrow;  // + 8*(e/4) + e%4
@@ -576,33 +581,35 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     //   workgroup (the first `rem` get q+1), so all do the same amount of work.  A run that does
     //   not cover a tile's whole reduction shares the tile with its neighbours in g: fix-up
     //   through the workspace if the host gave one, else atomics into zeroed y.
-    const int tiles = a.tiles_m * a.tiles_n;
+    // (tiles_dp, q = sk_q, rem = sk_rem and the divisors come from the host: they depend on the
+    // launch alone, and all of it fits 32 bits)
+    const int tiles = a.tiles;
     const bool persistent = a.persist > 0;
     const int G = gridDim.x, g = blockIdx.x;
-    const int tiles_dp = persistent ? tiles / G * G : 0;
-    const long long units = (long long)(tiles - tiles_dp) * a.nsteps;
-    const long long q = units / G, rem = units % G;
-    auto run_start = [&](long long gg) { return gg * q + (gg < rem ? gg : rem); };
-    auto owner_of = [&](long long u) {  // which workgroup's run holds unit u
-        if (u < rem * (q + 1)) return (int)(u / (q + 1));
-        return (int)(rem + (u - rem * (q + 1)) / (q > 0 ? q : 1));
+    const int tiles_dp = a.tiles_dp;
+    const int q = a.sk_q, rem = a.sk_rem;
+    auto run_start = [&](int gg) { return gg * q + (gg < rem ? gg : rem); };
+    auto owner_of = [&](int u) {  // which workgroup's run holds unit u
+        if (u < rem * (q + 1)) return fdiv(u, a.div_q1);
+        return rem + fdiv(u - rem * (q + 1), a.div_q0);
     };
     int next_dp = g;
-    long long u0 = persistent ? run_start(g) : 0;
-    const long long u1 = persistent ? run_start(g + 1) : 0;
+    int u0 = persistent ? run_start(g) : 0;
+    const int u1 = persistent ? run_start(g + 1) : 0;
     bool once = !persistent;
     for (;;) {
         int tile, kbeg, kend, mode = kStore, fix_j = 0, fix_slot = 0, fix_n = 1;
         if (once) {
             once = false;
             int bid = a.remap ? xcd_remap(g, G) : g;
-            tile = bid % tiles;
-            kbeg = (bid / tiles) * a.steps_per_split;
+            const int slice = fdiv(bid, a.div_tiles);
+            tile = bid - slice * tiles;
+            kbeg = slice * a.steps_per_split;
             kend = min(a.nsteps, kbeg + a.steps_per_split);
             if (a.split_k > 1) {
                 mode = a.ws ? kFixup : kAtomic;
                 fix_j = tile;
-                fix_slot = bid / tiles;
+                fix_slot = slice;
                 fix_n = a.split_k;
             }
         } else if (persistent && next_dp < tiles_dp) {
@@ -611,14 +618,14 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
             kend = a.nsteps;
             next_dp += G;
         } else if (persistent && u0 < u1) {
-            fix_j = (int)(u0 / a.nsteps);
+            fix_j = fdiv(u0, a.div_nsteps);
             tile = tiles_dp + fix_j;
-            kbeg = (int)(u0 - (long long)fix_j * a.nsteps);
-            kend = (int)min((long long)a.nsteps, kbeg + (u1 - u0));
+            kbeg = u0 - fix_j * a.nsteps;
+            kend = min(a.nsteps, kbeg + (u1 - u0));
             u0 += kend - kbeg;
             if (!(kbeg == 0 && kend == a.nsteps)) {
-                const int first = owner_of((long long)fix_j * a.nsteps);
-                fix_n = owner_of((long long)(fix_j + 1) * a.nsteps - 1) - first + 1;
+                const int first = owner_of(fix_j * a.nsteps);
+                fix_n = owner_of((fix_j + 1) * a.nsteps - 1) - first + 1;
                 fix_slot = g - first;
                 mode = a.ws ? kFixup : kAtomic;
             }

@@ -68,6 +68,24 @@ struct Problem {
 int make_problem(const wpk_conv_desc *d, Problem *out);  // WPK_OK or a WPK_E_* code
 std::string desc_key(const wpk_conv_desc *d);
 
+// Division of a 31-bit number by a launch constant as a multiply and a shift (the divisor's
+// multiplier is computed on the host): q = mulhi(n, mul) >> sh for d > 1.  With L = ceil(log2 d)
+// and mul = ceil(2^(31+L) / d), mul fits 32 bits and the quotient is exact for every n < 2^31.
+struct FastDiv {
+    uint32_t mul, sh, d;
+};
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f = {0, 0, d};
+    if (d > 1) {
+        uint32_t L = 0;
+        while ((1ull << L) < d) ++L;
+        f.mul = (uint32_t)((((uint64_t)1 << (31 + L)) + d - 1) / d);
+        f.sh = L - 1;
+    }
+    return f;
+}
+
 // Kernel argument block of the tiled implicit-GEMM family (passed by value).
 struct IgemmArgs {
     const float *x;
@@ -97,6 +115,12 @@ struct IgemmArgs {
     const float *bias;  // [K] or NULL
     const float *res;   // laid out like y, or NULL
     int32_t relu;       // act = max(., 0) when nonzero
+    // launch constants of the work iterator and their fast divisors
+    int32_t tiles;      // tiles_m * tiles_n
+    int32_t tiles_dp;   // persistent: tiles done whole, floor(tiles / G) * G
+    int32_t sk_q, sk_rem;  // persistent: the other tiles' steps in G runs of sk_q (+1 for the first sk_rem)
+    FastDiv div_pq, div_q, div_tiles_n, div_tiles, div_nsteps, div_q1, div_q0;  // by PQ, Q, tiles_n,
+                        // tiles, nsteps, sk_q + 1, max(sk_q, 1)
     int32_t xl;         // 0: x is [N][C][H][W]; 1: channels-last, gathered row by row; 2: channels-last,
                         // gathered as 16-byte channel quads (reduction rows ordered (r, s, c))
     int32_t yl;         // 1: y (and the residual) are channels-last; 2: also K % 4 == 0 and y, residual and

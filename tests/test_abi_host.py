@@ -4,6 +4,7 @@ constraint check, cache, search engine) behaves as the header says.  No compute 
 import ctypes
 import os
 import re
+import subprocess
 
 import numpy as np
 import pytest
@@ -306,3 +307,46 @@ def test_workspace_slots_cover_every_sharer_of_a_tile():
             assert nbytes == (1 << 20) + shared * slots * cfg.bm * cfg.bn * 4
             checked += 1
     assert checked > 100
+
+
+def test_fast_division_by_launch_constants(tmp_path):
+    """The kernels divide by launch constants with a host-computed multiplier and a shift; the
+    quotient must be exact for every dividend below 2^31.  Compiled from the library's own
+    header and checked against the plain quotient: every small pair, then edge and random ones."""
+    src = tmp_path / "fdiv.cpp"
+    src.write_text(r'''
+#include <cstdio>
+#include <cstdint>
+#include <string>
+#include <vector>
+#include "wpk_internal.h"
+static uint32_t q(uint32_t n, const wpk::FastDiv &f)
+{
+    return f.d == 1 ? n : (uint32_t)(((uint64_t)n * f.mul) >> 32) >> f.sh;
+}
+int main()
+{
+    uint64_t state = 12345, bad = 0, checked = 0;
+    auto rnd = [&]() { state = state * 6364136223846793005ull + 1442695040888963407ull; return (uint32_t)(state >> 33); };
+    for (uint32_t d = 1; d <= 3000; ++d) {
+        wpk::FastDiv f = wpk::make_fastdiv(d);
+        for (uint32_t n = 0; n <= 6000; ++n, ++checked) bad += q(n, f) != n / d;
+        for (uint32_t n : {0x7fffffffu, 0x7ffffffeu, 0x40000000u, d * 715827u, d * 715827u - 1})
+            if (n < 0x80000000u) { bad += q(n, f) != n / d; ++checked; }
+    }
+    for (int i = 0; i < 2000000; ++i, ++checked) {
+        uint32_t d = rnd() % 0x7fffffffu + 1, n = rnd() & 0x7fffffffu;
+        if (i & 1) d = d % 100000 + 1;
+        bad += q(n, wpk::make_fastdiv(d)) != n / d;
+    }
+    printf("%llu %llu\n", (unsigned long long)checked, (unsigned long long)bad);
+    return 0;
+}
+''')
+    exe = tmp_path / "fdiv"
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    subprocess.run(["g++", "-O1", "-std=c++17", "-I", os.path.join(root, "include"),
+                    "-I", os.path.join(root, "paper_2008_04567_amd", "csrc"), str(src), "-o", str(exe)], check=True)
+    checked, bad = [int(v) for v in subprocess.run([str(exe)], check=True, capture_output=True,
+                                                   text=True).stdout.split()]
+    assert checked > 10 ** 7 and bad == 0
