@@ -302,6 +302,18 @@ int64_t wpk_config_workspace_bytes(const wpk_conv_desc *d, const wpk_conv_config
 const char *wpk_config_kernel_name(const wpk_conv_config *cfg);
 /* Device name and compute-unit count of the current device. */
 int wpk_device_info(char *name, int32_t name_capacity, int32_t *compute_units);
+/* Measured ceilings of the current device, for reporting beside the published ones (calibration, no
+ * part of the operator; sustained clocks under matrix load lie below the peak engine clock).
+ *   mfma_tflops_burst     : one 0.3 ms launch of an fp32 MFMA-only kernel (32x32x2, four independent
+ *                           accumulators per wave, two waves per SIMD, varied operands) right after a
+ *                           20 ms pause: clock ramp-up and launch latency included
+ *   mfma_tflops_sustained : the same kernel launched back to back for sustain_ms (0 .. 10000) in all;
+ *                           the rate over the second half
+ *   copy_gbs              : bytes read plus bytes written per second by a 16-byte-per-lane copy of 256 MiB
+ * Any of the three pointers may be NULL (that measurement is skipped; host pointers otherwise).
+ * Allocates and frees its own device buffers, enqueues on `stream` and synchronises it. */
+int wpk_measure_peaks(double sustain_ms, double *mfma_tflops_burst, double *mfma_tflops_sustained,
+                      double *copy_gbs, void *stream);
 /* Library version string. */
 const char *wpk_version(void);
 

@@ -135,6 +135,7 @@ def lib():
             "wpk_config_kernel_name": (ctypes.c_char_p, [P(ConvConfig)]),
             "wpk_device_info": (I, [ctypes.c_char_p, ctypes.c_int32, i32p]),
             "wpk_version": (ctypes.c_char_p, []),
+            "wpk_measure_peaks": (I, [D, P(D), P(D), P(D), V]),
             "wpk_set_workspace_limit": (I, [ctypes.c_int64]),
             "wpk_config_workspace_bytes": (ctypes.c_int64, [P(ConvDesc), P(ConvConfig), ctypes.c_int32,
                                                             P(ctypes.c_int64), P(ctypes.c_int64)]),
@@ -465,6 +466,15 @@ def config_workspace(desc, cfg, compute_units=256):
 
 def set_workspace_limit(nbytes):
     _check(lib().wpk_set_workspace_limit(int(nbytes)), "wpk_set_workspace_limit")
+
+
+def measure_peaks(sustain_ms=60.0, stream=None):
+    """Measured ceilings of the device: (fp32 MFMA TFLOP/s right after a pause, sustained over the
+    second half of sustain_ms, copy GB/s read + written)."""
+    burst, sustained, copy = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    _check(lib().wpk_measure_peaks(float(sustain_ms), ctypes.byref(burst), ctypes.byref(sustained),
+                                   ctypes.byref(copy), _stream(stream)), "wpk_measure_peaks")
+    return burst.value, sustained.value, copy.value
 
 
 def device_info():

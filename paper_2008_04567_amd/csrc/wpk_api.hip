@@ -10,6 +10,7 @@
 #include <map>
 #include <mutex>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "wpk_igemm.h"
@@ -172,6 +173,49 @@ __global__ void compare_kernel(const float *__restrict__ y, const float *__restr
         worst = fmaxf(worst, e);
     }
     atomicMax(out_bits, __float_as_uint(worst));
+}
+
+// ---- calibration kernels (measured ceilings reported beside the published ones) ----------------------
+// Nothing but fp32 MFMAs: four independent accumulators per wave, so an MFMA never waits for the one
+// before it, and sixteen operand pairs of hashed values in [0,1) x [-0.5,0.5) (operands that never
+// change make the figure unrepresentative: at four waves per SIMD they measure 20 % low here).
+__device__ inline float unit_hash(unsigned x)
+{
+    x ^= x >> 16;
+    x *= 0x7feb352dU;
+    x ^= x >> 15;
+    x *= 0x846ca68bU;
+    x ^= x >> 16;
+    return (float)(x >> 8) * (1.0f / 16777216.0f);
+}
+
+__global__ void __launch_bounds__(256) mfma_only_kernel(float *out, int iters)
+{
+    v16f acc[4];
+    for (int i = 0; i < 4; ++i)
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    float a[16], b[16];
+    for (int i = 0; i < 16; ++i) {
+        a[i] = unit_hash(blockIdx.x * 4096u + threadIdx.x * 16u + i);
+        b[i] = unit_hash(0x9e3779b9u + threadIdx.x * 16u + i) - 0.5f;
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+            acc[u & 3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], acc[u & 3], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int i = 0; i < 4; ++i)
+        for (int e = 0; e < 16; ++e) s += acc[i][e];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+// Streaming copy, 16 bytes per lane per trip.
+__global__ void __launch_bounds__(256) copy16_kernel(const float4 *__restrict__ src, float4 *__restrict__ dst,
+                                                     long long n16)
+{
+    const long long stride = (long long)gridDim.x * 256;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
 // ---- device state -----------------------------------------------------------------------------------
@@ -689,6 +733,70 @@ int wpk_device_info(char *name, int32_t cap, int32_t *cus)
         name[cap - 1] = 0;
     }
     if (cus) *cus = g_cus;
+    return WPK_OK;
+}
+
+int wpk_measure_peaks(double sustain_ms, double *mfma_burst, double *mfma_sustained, double *copy_gbs, void *stream)
+{
+    std::lock_guard<std::mutex> g(g_mu);
+    int rc = ensure_device();
+    if (rc != WPK_OK) return rc;
+    if (!(sustain_ms >= 0.0) || sustain_ms > 10000.0) return WPK_E_BAD_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const int blocks = 2 * g_cus, iters = 350;          // about 0.3 ms per launch at 2.4 GHz
+    const double flop = (double)blocks * 4 * iters * 16 * 4096.0;
+    const long long copy_bytes = 256ll << 20;
+    float *out = nullptr, *src = nullptr, *dst = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t err = hipSuccess;
+    auto ok = [&](hipError_t e) { if (err == hipSuccess) err = e; return err == hipSuccess; };
+    float ms = 0.f;
+    if (ok(hipMalloc((void **)&out, (size_t)blocks * 256 * 4)) && ok(hipEventCreate(&e0)) && ok(hipEventCreate(&e1))) {
+        if (mfma_burst || mfma_sustained) {
+            // clocks settle high while the device idles: one launch right after a pause
+            hipLaunchKernelGGL(mfma_only_kernel, dim3(blocks), dim3(256), 0, st, out, 8);
+            ok(hipStreamSynchronize(st));
+            std::this_thread::sleep_for(std::chrono::milliseconds(20));
+            ok(hipEventRecord(e0, st));
+            hipLaunchKernelGGL(mfma_only_kernel, dim3(blocks), dim3(256), 0, st, out, iters);
+            ok(hipEventRecord(e1, st));
+            ok(hipEventSynchronize(e1));
+            if (ok(hipEventElapsedTime(&ms, e0, e1)) && mfma_burst) *mfma_burst = flop / (ms * 1e-3) / 1e12;
+            // then back-to-back launches for sustain_ms; the rate of the second half counts
+            const int half = std::max(1, (int)(sustain_ms / 0.3 / 2));
+            for (int i = 0; i < half; ++i) hipLaunchKernelGGL(mfma_only_kernel, dim3(blocks), dim3(256), 0, st, out, iters);
+            ok(hipEventRecord(e0, st));
+            for (int i = 0; i < half; ++i) hipLaunchKernelGGL(mfma_only_kernel, dim3(blocks), dim3(256), 0, st, out, iters);
+            ok(hipEventRecord(e1, st));
+            ok(hipEventSynchronize(e1));
+            if (ok(hipEventElapsedTime(&ms, e0, e1)) && mfma_sustained)
+                *mfma_sustained = flop * half / (ms * 1e-3) / 1e12;
+        }
+        if (copy_gbs && ok(hipMalloc((void **)&src, copy_bytes)) && ok(hipMalloc((void **)&dst, copy_bytes)) &&
+            ok(hipMemsetAsync(src, 0, copy_bytes, st))) {
+            const int reps = 5;
+            hipLaunchKernelGGL(copy16_kernel, dim3(g_cus * 8), dim3(256), 0, st, (const float4 *)src, (float4 *)dst,
+                               copy_bytes / 16);
+            ok(hipEventRecord(e0, st));
+            for (int i = 0; i < reps; ++i)
+                hipLaunchKernelGGL(copy16_kernel, dim3(g_cus * 8), dim3(256), 0, st, (const float4 *)src,
+                                   (float4 *)dst, copy_bytes / 16);
+            ok(hipEventRecord(e1, st));
+            ok(hipEventSynchronize(e1));
+            if (ok(hipEventElapsedTime(&ms, e0, e1))) *copy_gbs = 2.0 * copy_bytes * reps / (ms * 1e-3) / 1e9;
+        }
+        ok(hipGetLastError());
+    }
+    (void)hipStreamSynchronize(st);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (out) (void)hipFree(out);
+    if (src) (void)hipFree(src);
+    if (dst) (void)hipFree(dst);
+    if (err != hipSuccess) {
+        set_last_hip_error((int)err);
+        return WPK_E_HIP;
+    }
     return WPK_OK;
 }
 

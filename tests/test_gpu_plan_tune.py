@@ -266,3 +266,17 @@ def test_plan_run_can_be_captured_in_a_hip_graph(ways):
             check("eager after replay %d" % rep)
     del g
     plan.destroy()
+
+
+def test_measured_peaks_are_plausible_and_skippable():
+    """The calibration entry point: an MFMA-only kernel cannot exceed the published fp32 matrix peak
+    (256 CUs x 256 FLOP per clock x 2.4 GHz) by more than clock tolerance, and a copy stays under the
+    HBM peak.  (Which of the two MFMA figures is larger depends on how fast the clocks ramp.)"""
+    burst, sustained, copy = B.measure_peaks(20.0)
+    assert 40.0 < sustained < 1.1 * 157.3
+    assert 40.0 < burst < 1.1 * 157.3
+    assert 200.0 < copy < 8000.0
+    # NULL outputs skip measurements; arguments out of range are refused
+    assert B.lib().wpk_measure_peaks(0.0, None, None, None, None) == 0
+    assert B.lib().wpk_measure_peaks(-1.0, None, None, None, None) == B.E_BAD_ARG
+    assert B.lib().wpk_measure_peaks(1e9, None, None, None, None) == B.E_BAD_ARG
