@@ -369,6 +369,7 @@ static int fixup_reserve(FixupBuf &b, size_t bytes)
     b.bytes = 0;
     WPK_HIP(hipMalloc((void **)&b.ptr, bytes));
     WPK_HIP(hipMemset(b.ptr, 0, kFixupCounterBytes));
+    WPK_HIP(hipDeviceSynchronize());  // filled before a launch on any stream can follow
     b.bytes = bytes;
     return WPK_OK;
 }
