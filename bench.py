@@ -62,7 +62,17 @@ def cpu_baseline(W, layers, max_seconds=25.0):
         done.append(l["name"])
         if secs > max_seconds:
             break
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
     out = {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": int(used), "kind": "oracle",
+           "cpu_model": model, "host_cpus": os.cpu_count(),
            "sample": "%d of %d layers, full batch, fp64 seven-loop, %.1f s wall: %s"
                      % (len(done), len(layers), secs, ",".join(done))}
     # the same oracle on one thread, on the first two images of the first layer

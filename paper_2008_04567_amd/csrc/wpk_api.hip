@@ -424,8 +424,10 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     a.tiles_dp = cfg.persist > 0 ? a.tiles / a.grid_persist * a.grid_persist : 0;
     {
         int64_t units = (int64_t)(a.tiles - a.tiles_dp) * a.nsteps;  // < 2^31: checked by legal_for
-        a.sk_q = cfg.persist > 0 ? (int32_t)(units / a.grid_persist) : 0;
-        a.sk_rem = cfg.persist > 0 ? (int32_t)(units % a.grid_persist) : 0;
+        int64_t groups = cfg.persist > 0 ? streamk_groups(units, a.grid_persist, cfg.bk) : 0;
+        a.sk_groups = (int32_t)groups;
+        a.sk_q = groups > 0 ? (int32_t)(units / groups) : 0;
+        a.sk_rem = groups > 0 ? (int32_t)(units % groups) : 0;
     }
     a.div_pq = make_fastdiv((uint32_t)a.PQ);
     a.div_q = make_fastdiv((uint32_t)a.Q);

@@ -182,12 +182,13 @@ FixupNeed fixup_need(const Problem &pr, const wpk_conv_config &cfg, int compute_
     int64_t tiles = ((pr.M + cfg.bm - 1) / cfg.bm) * ((pr.d.k + cfg.bn - 1) / cfg.bn);
     int64_t nsteps = (pr.CRS + cfg.bk - 1) / cfg.bk;
     if (cfg.persist > 0) {
-        // tiles of the last partial round, their steps dealt in G runs of q or q+1: a tile's
-        // nsteps steps meet at most ceil((nsteps-1)/q)+1 runs, and never more than nsteps
+        // tiles of the last partial round, their steps dealt in runs of q or q+1 to at most G
+        // workgroups: a tile's nsteps steps meet at most ceil((nsteps-1)/q)+1 runs, and never
+        // more than nsteps
         int64_t G = (int64_t)cfg.persist * compute_units;
         int64_t shared = tiles - tiles / G * G;
         if (shared == 0 || nsteps <= 1) return n;
-        int64_t q = shared * nsteps / G;
+        int64_t q = shared * nsteps / streamk_groups(shared * nsteps, G, cfg.bk);
         n.shared_tiles = shared;
         n.maxc = q > 0 ? std::min<int64_t>(nsteps, (nsteps - 1 + q - 1) / q + 1) : nsteps;
     } else {

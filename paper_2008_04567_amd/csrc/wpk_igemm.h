@@ -577,12 +577,13 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     //   of a tile meet through the workspace if the host gave one, else through atomics.
     // persist  > 0: gridDim.x = G persistent workgroups.  Each first takes whole tiles g, g+G, ...
     //   of the first tiles_dp = floor(tiles/G)*G tiles.  The reduction steps of the remaining
-    //   tiles, laid end to end (`units` of them), are cut into G runs of q or q+1 steps, one per
-    //   workgroup (the first `rem` get q+1), so all do the same amount of work.  A run that does
+    //   tiles, laid end to end (`units` of them), are cut into runs of q or q+1 steps (the first
+    //   `rem` get q+1), one for each of the first sk_groups workgroups: all G of them, unless
+    //   that would make the runs too short to be worth a prologue.  A run that does
     //   not cover a tile's whole reduction shares the tile with its neighbours in g: fix-up
     //   through the workspace if the host gave one, else atomics into zeroed y.
-    // (tiles_dp, q = sk_q, rem = sk_rem and the divisors come from the host: they depend on the
-    // launch alone, and all of it fits 32 bits)
+    // (tiles_dp, sk_groups, q = sk_q, rem = sk_rem and the divisors come from the host: they
+    // depend on the launch alone, and all of it fits 32 bits)
     const int tiles = a.tiles;
     const bool persistent = a.persist > 0;
     const int G = gridDim.x, g = blockIdx.x;
@@ -594,8 +595,9 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
         return rem + fdiv(u - rem * (q + 1), a.div_q0);
     };
     int next_dp = g;
-    int u0 = persistent ? run_start(g) : 0;
-    const int u1 = persistent ? run_start(g + 1) : 0;
+    const bool dealt = persistent && g < a.sk_groups;
+    int u0 = dealt ? run_start(g) : 0;
+    const int u1 = dealt ? run_start(g + 1) : 0;
     bool once = !persistent;
     for (;;) {
         int tile, kbeg, kend, mode = kStore, fix_j = 0, fix_slot = 0, fix_n = 1;

@@ -262,7 +262,8 @@ def test_workspace_limit_argument_check():
 def test_workspace_slots_cover_every_sharer_of_a_tile():
     """The kernel indexes a shared tile's slots by the position of a workgroup among the tile's
     sharers.  Re-derive the sharers from the schedule's definition (persistent: the steps of the
-    tiles beyond the last whole round, laid end to end and cut into G runs of q or q+1; split:
+    tiles beyond the last whole round, laid end to end and cut into runs of q or q+1, one for each
+    of the first min(G, units / max(1, 64 / BK)) workgroups; split:
     the non-empty slices) and check that the slot count the host reserves is never too small."""
     rng = np.random.default_rng(5)
     checked = 0
@@ -289,10 +290,11 @@ def test_workspace_slots_cover_every_sharer_of_a_tile():
                 G = cfg.persist * cus
                 rest = tiles - tiles // G * G
                 units = rest * nsteps
-                q, rem = divmod(units, G)
+                groups = min(G, max(1, units // max(1, 64 // cfg.bk))) if units else 0   # runs of >= 64 rows
+                q, rem = divmod(units, groups) if groups else (0, 0)
                 start = lambda g: g * q + min(g, rem)
                 owners = [0] * rest
-                for g in range(G):            # every run marks the tiles it touches
+                for g in range(groups):       # every run marks the tiles it touches
                     u0, u1 = start(g), start(g + 1)
                     if u1 > u0:
                         for j in range(u0 // nsteps, (u1 - 1) // nsteps + 1):
