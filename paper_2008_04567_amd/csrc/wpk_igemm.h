@@ -72,6 +72,12 @@ __device__ __forceinline__ int fdiv(int n, const FastDiv &f)
     return f.d == 1 ? n : (int)(__umulhi((unsigned)n, f.mul) >> f.sh);
 }
 
+// Cache policy of the stores of y: sc0 | sc1, written through the per-XCD L2 as they are issued.
+// With the default policy the outputs sit dirty in the L2s until the kernel ends and are written
+// back then, before the next dispatch may start; nobody in this launch reads them again.  Measured:
+// 0.8 us per launch on a layer that writes 12.8 MB, nothing on small outputs.
+constexpr int kYStorePolicy = 17;
+
 // The tap table is read through the constant address space: wave-uniform scalar loads.
 typedef const int __attribute__((address_space(4))) *tap_ptr;
 
@@ -518,7 +524,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                                               fmaxf(v[3], 0.0f)};
                             }
                             __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), yrsrc, voff,
-                                                                   32 * g, 0);
+                                                                   32 * g, kYStorePolicy);
                         }
                     });
                 } else if (fused) {
@@ -544,7 +550,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                             float v = acc[i * NMT + j][e] + add[e];
                             v = a.relu ? fmaxf(v, 0.0f) : v;
                             __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
-                                                                  voff, de * PQ4, 0);
+                                                                  voff, de * PQ4, kYStorePolicy);
                         }
                     });
                 } else if (atomic) {
@@ -563,7 +569,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                             // reads element 0 with this compiler
                             const float v = acc[i * NMT + j][e];
                             __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
-                                                                  voff, de * PQ4, 0);
+                                                                  voff, de * PQ4, kYStorePolicy);
                         }
                     });
                 }
