@@ -226,6 +226,22 @@ void default_config(const Problem &pr, int compute_units, wpk_conv_config *out)
     int64_t want = std::min<int64_t>((7 * (int64_t)compute_units / 2 + tiles / 2) / tiles, nsteps / 4);
     for (int i = 0; i < kGeneCounts[5]; ++i)
         if (kSplitVals[i] <= want) c.split_k = kSplitVals[i];
+    // Just over a whole number of rounds of three workgroups per compute unit: persistent
+    // workgroups run the rounds as whole tiles and deal out only the few tiles left over,
+    // instead of a last round that leaves most of the device idle.
+    int64_t G = 3 * (int64_t)compute_units;
+    if (tiles > G && tiles % G != 0 && (tiles % G) * 8 <= G) {
+        wpk_conv_config h = c;
+        h.bk = pr.CRS >= 32 ? 16 : 8;
+        h.split_k = 1;
+        h.xcd_remap = 0;
+        h.persist = 3;
+        h.reduce = 0;
+        if (legal_for(pr, h)) {
+            *out = h;
+            return;
+        }
+    }
     // atomics where many slices meet in a small output (zeroing it is cheap and the last
     // workgroup need not read every slot); the workspace otherwise
     int64_t per = (nsteps + c.split_k - 1) / c.split_k, slices = (nsteps + per - 1) / per;
