@@ -371,14 +371,16 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     using std::false_type;
     using std::true_type;
 
-    // prologue: tile 0 straight into LDS buffer 0, tiles 1..PD into their staging sets
+    // prologue: the loads of tiles 0..PD-1 are all issued before anything waits (one memory
+    // latency, not two); then tile 0 goes to LDS buffer 0 and tile PD into the set it frees
     const int nr = kend - kbeg;
     load_tile(std::integral_constant<int, 0>{}, kbeg);
-    store_tile(std::integral_constant<int, 0>{}, 0);
-    static_for<PD>([&](auto P) WPK_LAMBDA {
+    static_for<PD - 1>([&](auto P) WPK_LAMBDA {
         constexpr int t = decltype(P)::value + 1;
-        if (t < nr) load_tile(std::integral_constant<int, t % PD>{}, kbeg + t);
+        if (t < nr) load_tile(std::integral_constant<int, t>{}, kbeg + t);
     });
+    store_tile(std::integral_constant<int, 0>{}, 0);
+    if (PD < nr) load_tile(std::integral_constant<int, 0>{}, kbeg + PD);
     __syncthreads();
     int r = 0;
     // main loop: every step still has a tile to store (r+1) and one to load (r+1+PD)
