@@ -159,6 +159,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     //        bit 31 is always set and is what the table's padding rows point at.
     int xvoff[XP];
     unsigned xinv[XP];
+    auto gather_state = [&]() WPK_LAMBDA {
     static_for<XP>([&](auto I) WPK_LAMBDA {
         constexpr int i = decltype(I)::value;
         int m = m0 + pm0 + i * T;
@@ -182,6 +183,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
             xinv[i] = inv;
         }
     });
+    };
     const int wvoff = (wkq * a.Kpad + n0 + wkout) * 16;
 
     // ---- staging registers: PD tiles (activations and weights) in flight between global memory
@@ -373,8 +375,13 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
 
     // prologue: the loads of tiles 0..PD-1 are all issued before anything waits (one memory
     // latency, not two); then tile 0 goes to LDS buffer 0 and tile PD into the set it frees
+    // (tile 0: the scalar tap loads and the weight loads, which depend on the tile alone, are
+    // issued first; the per-pixel gather state is computed while they are in flight)
     const int nr = kend - kbeg;
-    load_tile(std::integral_constant<int, 0>{}, kbeg);
+    load_taps(kbeg);
+    static_for<NW>([&](auto E) WPK_LAMBDA { load_w(std::integral_constant<int, 0>{}, kbeg, E); });
+    gather_state();
+    static_for<NXL>([&](auto E) WPK_LAMBDA { load_x(std::integral_constant<int, 0>{}, E); });
     static_for<PD - 1>([&](auto P) WPK_LAMBDA {
         constexpr int t = decltype(P)::value + 1;
         if (t < nr) load_tile(std::integral_constant<int, t>{}, kbeg + t);
