@@ -247,8 +247,8 @@ def main():
             plan.run_layer_fused(i, xs[c][i], rs[c][i], ys[c][i], stream)
             ev[s][i + 1].record(stream)
     torch.cuda.synchronize()
-    per_layer_us = [1e3 * float(np.mean([ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(args.steps)]))
-                    for i in range(n)]
+    samples_us = [[1e3 * ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(args.steps)] for i in range(n)]
+    per_layer_us = [float(np.mean(v)) for v in samples_us]
     rows = []
     for i, l in enumerate(layers):
         cfg = plan.layer_config(i)
@@ -263,7 +263,8 @@ def main():
         rows.append({"layer": l["name"], "kernel": B.config_kernel_name(cfg), "split_k": cfg.split_k,
                      "xcd_remap": cfg.xcd_remap, "persist": cfg.persist, "stages": cfg.stages,
                      "reduce": "atomics" if cfg.reduce else "workspace",
-                     "us": round(per_layer_us[i], 2),
+                     "us": round(per_layer_us[i], 2), "us_median": round(float(np.median(samples_us[i])), 2),
+                     "us_min": round(float(np.min(samples_us[i])), 2),
                      "tflops": round(tf, 2), "pct_fp32_mfma_peak": round(100 * tf / FP32_MFMA_PEAK_TFLOPS, 1),
                      "gbs_algorithmic": round(gbs, 1), "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1),
                      "bound": bound, "flops": flops[i], "bytes_algorithmic": abytes})
