@@ -247,7 +247,11 @@ int wpk_plan_set_weights(wpk_plan *plan, int32_t layer, const float *w, void *st
  * waits): they allocate nothing and may be recorded by a stream capture into a HIP graph. */
 /* Run every layer in order on `stream`: y[i] = conv(x[i], weights of layer i).  x and y are HOST
  * arrays of n_layers DEVICE pointers.  Weights of every layer must have been set.  A layer with
- * an epilogue (wpk_plan_set_epilogue) applies it. */
+ * an epilogue (wpk_plan_set_epilogue) applies it.  Tensors may be shared between layers in any way
+ * a layer-by-layer run allows (an output feeding later layers, buffers reused in turns): outputs
+ * that a layer accumulates into with atomics are zeroed by a single launch at the start of the
+ * pass only where they overlap nothing that an earlier layer of the pass reads or writes, and
+ * right before their layer otherwise. */
 int wpk_plan_run(wpk_plan *plan, const float *const *x, float *const *y, void *stream);
 
 /* Run one layer of the plan. */

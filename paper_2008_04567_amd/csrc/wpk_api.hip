@@ -175,6 +175,37 @@ __global__ void compare_kernel(const float *__restrict__ y, const float *__restr
     atomicMax(out_bits, __float_as_uint(worst));
 }
 
+// Zero several tensors with one launch: entry e covers blocks [first[e], first[e+1]), each block
+// 1024 sixteen-byte quads of the tensor's aligned body; block 0 of an entry also clears the few
+// floats before and after the body.
+static const int kZeroListMax = 48;
+struct ZeroList {
+    float *p[kZeroListMax];
+    long long n[kZeroListMax];
+    int first[kZeroListMax + 1];
+    int count;
+};
+__global__ void __launch_bounds__(256) zero_many_kernel(const ZeroList z)
+{
+    int e = 0;
+    while (e + 1 < z.count && (int)blockIdx.x >= z.first[e + 1]) ++e;
+    const int b = blockIdx.x - z.first[e];
+    float *p = z.p[e];
+    const long long n = z.n[e];
+    long long head = (long long)(((16 - ((unsigned long long)p & 15)) & 15) / 4);
+    if (head > n) head = n;
+    const long long n4 = (n - head) / 4, tail = n - head - n4 * 4;
+    float4 *p4 = (float4 *)(p + head);
+    for (int u = 0; u < 4; ++u) {
+        long long j = (long long)b * 1024 + u * 256 + threadIdx.x;
+        if (j < n4) p4[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (b == 0) {
+        if ((long long)threadIdx.x < head) p[threadIdx.x] = 0.0f;
+        if ((long long)threadIdx.x < tail) p[head + n4 * 4 + threadIdx.x] = 0.0f;
+    }
+}
+
 // ---- calibration kernels (measured ceilings reported beside the published ones) ----------------------
 // Nothing but fp32 MFMAs: four independent accumulators per wave, so an MFMA never waits for the one
 // before it, and sixteen operand pairs of hashed values in [0,1) x [-0.5,0.5) (operands that never
@@ -383,9 +414,28 @@ static void fixup_release(FixupBuf &b)
 // Launch one member of the tiled family.  cfg must be legal for pr (checked by the callers).
 // `fix` is the fix-up workspace of a persistent launch, large enough for fixup_need(); with a
 // NULL workspace shared tiles are accumulated with atomics into zeroed outputs.
+// Whether a launch of cfg accumulates into all of y with atomics, so that all of y has to be
+// zeroed first (no workspace that covers it, and a split reduction or a persistent launch without
+// a whole round).
+static bool zeroes_all_of_y(const Problem &pr, const wpk_conv_config &cfg, const FixupBuf *fix)
+{
+    FixupNeed need = fixup_need(pr, cfg, g_cus);
+    if (need.bytes > 0 && fix && fix->ptr && fix->bytes >= (size_t)need.bytes) return false;
+    int nsteps = (pr.CRS + cfg.bk - 1) / cfg.bk;
+    int per = (nsteps + cfg.split_k - 1) / cfg.split_k;
+    if ((nsteps + per - 1) / per > 1) return true;
+    if (cfg.persist > 0) {
+        int64_t tiles = ((pr.M + cfg.bm - 1) / cfg.bm) * ((pr.d.k + cfg.bn - 1) / cfg.bn);
+        int64_t G = (int64_t)cfg.persist * (g_cus > 0 ? g_cus : 256);
+        return tiles < G;
+    }
+    return false;
+}
+
+// (y_zeroed: the caller has already zeroed all of y on this stream)
 static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32_t *ktab,
                       const float *x, const float *wp, float *y, const FixupBuf *fix, hipStream_t st,
-                      const Epilogue &epi = Epilogue())
+                      const Epilogue &epi = Epilogue(), bool y_zeroed = false)
 {
     int vi = find_variant(cfg.bm, cfg.bn, cfg.bk, cfg.wm, cfg.wn, cfg.stages);
     if (vi < 0) return WPK_E_NO_CONFIG;
@@ -452,7 +502,7 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     a.res = shared_by_atomics ? nullptr : epi.res;
     a.relu = shared_by_atomics ? 0 : epi.relu;
     if (a.split_k > 1 && !a.ws) {
-        int rc = zero_fill(y, pr.y_elems, st);
+        int rc = y_zeroed ? WPK_OK : zero_fill(y, pr.y_elems, st);
         if (rc != WPK_OK) return rc;
     } else if (a.split_k == 1 && cfg.persist > 0 && !a.ws) {
         // tiles beyond the last whole round are accumulated with atomics: zero their pixels
@@ -461,7 +511,7 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
         if (tiles_dp < tiles) {
             int m_begin = tiles_dp / a.tiles_n * cfg.bm;
             if (m_begin == 0) {
-                int rc = zero_fill(y, pr.y_elems, st);
+                int rc = y_zeroed ? WPK_OK : zero_fill(y, pr.y_elems, st);
                 if (rc != WPK_OK) return rc;
             } else {
                 long long n = (long long)(a.M - m_begin) * a.K;
@@ -1135,7 +1185,7 @@ int wpk_plan_set_epilogue(wpk_plan *plan, int32_t layer, const float *bias, int3
 
 // One layer (or, with which = 0/1, one half-batch of it) on stream st.
 static int plan_launch(wpk_plan *plan, wpk_plan::Layer &L, int which, const float *x,
-                       const float *residual, float *y, hipStream_t st)
+                       const float *residual, float *y, hipStream_t st, bool y_zeroed = false)
 {
     const Problem &pr = which < 0 ? L.pr : L.half[which];
     const wpk_conv_config &cfg = which < 0 ? L.cfg : L.half_cfg[which];
@@ -1151,7 +1201,7 @@ static int plan_launch(wpk_plan *plan, wpk_plan::Layer &L, int which, const floa
         return rc != WPK_OK ? rc : run_epilogue(pr, epi, y, st);
     }
     return run_config(pr, cfg, plan->ktabs[L.unique], x, L.wp, y, which == 1 ? &plan->fix_side : &plan->fix,
-                      st, epi);
+                      st, epi, y_zeroed);
 }
 
 static int plan_fork(wpk_plan *plan, hipStream_t user)
@@ -1229,12 +1279,56 @@ int wpk_plan_run_fused(wpk_plan *plan, const float *const *x, const float *const
 {
     if (!plan || !x || !y) return WPK_E_NULL_PTR;
     if (plan->ways == 1) {
-        for (size_t i = 0; i < plan->layers.size(); ++i) {
-            int rc = wpk_plan_run_layer_fused(plan, (int32_t)i, x[i], residual ? residual[i] : nullptr,
-                                              y[i], stream);
-            if (rc != WPK_OK) return rc;
+        const size_t nl = plan->layers.size();
+        for (size_t i = 0; i < nl; ++i)
+            if (!x[i] || !y[i]) return WPK_E_NULL_PTR;
+            else if (!plan->layers[i].has_w) return WPK_E_BAD_ARG;
+        // Outputs that their layer accumulates into with atomics have to be zero beforehand.  All
+        // pointers of the pass are known here, so those outputs are zeroed by one launch up front
+        // instead of one launch each -- but only an output that overlaps nothing an earlier layer
+        // of the pass reads or writes, nor its own layer's inputs; the others are zeroed right
+        // before their layer as usual.
+        auto overlaps = [](const float *p, int64_t n, const float *q, int64_t m) {
+            return p && q && (uintptr_t)p < (uintptr_t)(q + m) && (uintptr_t)q < (uintptr_t)(p + n);
+        };
+        std::vector<char> ahead(nl, 0);
+        ZeroList z;
+        z.count = 0;
+        z.first[0] = 0;
+        hipStream_t st = (hipStream_t)stream;
+        auto flush = [&]() -> int {
+            if (z.count == 0) return WPK_OK;
+            hipLaunchKernelGGL(zero_many_kernel, dim3(z.first[z.count]), dim3(256), 0, st, z);
+            z.count = 0;
+            WPK_HIP(hipGetLastError());
+            return WPK_OK;
+        };
+        for (size_t j = 0; j < nl; ++j) {
+            const wpk_plan::Layer &L = plan->layers[j];
+            if (L.direct || !zeroes_all_of_y(L.pr, L.cfg, &plan->fix)) continue;
+            const int64_t ny = L.pr.y_elems;
+            bool ok = !overlaps(y[j], ny, x[j], L.pr.x_elems) &&
+                      !(residual && overlaps(y[j], ny, residual[j], ny));
+            for (size_t i = 0; i < j && ok; ++i) {
+                const Problem &pi = plan->layers[i].pr;
+                ok = !overlaps(y[j], ny, x[i], pi.x_elems) && !overlaps(y[j], ny, y[i], pi.y_elems) &&
+                     !(residual && overlaps(y[j], ny, residual[i], pi.y_elems));
+            }
+            if (!ok) continue;
+            ahead[j] = 1;
+            z.p[z.count] = y[j];
+            z.n[z.count] = ny;
+            z.first[z.count + 1] = z.first[z.count] + (int)std::max<int64_t>(1, (ny / 4 + 1023) / 1024);
+            if (++z.count == kZeroListMax) {
+                int rc = flush();
+                if (rc != WPK_OK) return rc;
+            }
         }
-        return WPK_OK;
+        int rc = flush();
+        for (size_t i = 0; i < nl && rc == WPK_OK; ++i)
+            rc = plan_launch(plan, plan->layers[i], -1, x[i], residual ? residual[i] : nullptr, y[i], st,
+                             ahead[i] != 0);
+        return rc;
     }
     // two chains of half-batches: one on the caller's stream, one on the plan's, forked and
     // joined once around the whole pass
