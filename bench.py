@@ -142,7 +142,10 @@ def main():
         log("loaded %d cached search results" % B.cache_load(args.cache))
     t_tune = time.perf_counter()
     if not args.no_tune:
-        opt = B.tune_default_options(mode=args.tune_mode, verbose=1 if args.verbose_tune else 0)
+        # the timed region runs whole passes of a plan on separate buffers: outputs that a layer sums
+        # into with atomics are zeroed once per pass, so candidates are timed without that launch
+        opt = B.tune_default_options(mode=args.tune_mode, verbose=1 if args.verbose_tune else 0,
+                                     zero_ahead=0 if args.pipeline == 2 else 1)
         if args.refine is not None:
             opt.refine = args.refine
         seen = set()

@@ -179,6 +179,10 @@ typedef struct wpk_tune_options {
                              fastest candidates are timed again in groups of at least 4 ms
                              (clocks settled under load) and the fastest kept; not part of
                              the paper's search; 0 = off, default 2                               */
+    int32_t zero_ahead;   /* how candidates that accumulate into y with atomics are timed: 0 (default)
+                             with the launch that zeroes y, as a single call pays it; 1 without it,
+                             as in a plan run as whole passes, which zeroes such outputs once per pass
+                             ahead of the layers (wpk_plan_run)                                   */
 } wpk_tune_options;
 
 /* Fill `o` with the defaults above. */

@@ -48,7 +48,8 @@ class TuneOptions(ctypes.Structure):
                 ("mutation", ctypes.c_double), ("eps", ctypes.c_double),
                 ("seed", ctypes.c_uint64), ("reps", ctypes.c_int32),
                 ("min_group_us", ctypes.c_double), ("mode", ctypes.c_int32),
-                ("verbose", ctypes.c_int32), ("refine", ctypes.c_int32)]
+                ("verbose", ctypes.c_int32), ("refine", ctypes.c_int32),
+                ("zero_ahead", ctypes.c_int32)]
 
 
 class TuneReport(ctypes.Structure):
