@@ -69,7 +69,7 @@ __device__ __forceinline__ void static_for(F &&f)
 
 __device__ __forceinline__ int fdiv(int n, const FastDiv &f)
 {
-    return f.d == 1 ? n : (int)(__umulhi((unsigned)n, f.mul) >> f.sh);
+    return (int)((__umulhi((unsigned)n, f.mul) + (unsigned)n) >> f.sh);
 }
 
 // Cache policy of the stores of y: sc0 | sc1, written through the per-XCD L2 as they are issued.
@@ -563,12 +563,13 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                         }
                     });
                 } else if (atomic) {
-                    float *yp = a.yl ? a.y + (size_t)m * a.K : a.y + (size_t)n * a.K * a.PQ + pq;
-                    const size_t ks = a.yl ? 1 : (size_t)a.PQ;
+                    // (no-return fp32 adds, addressed like the stores)
                     static_for<16>([&](auto E) WPK_LAMBDA {
                         constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
-                        if (kbase + de < a.K)
-                            unsafeAtomicAdd(yp + (size_t)(kbase + de) * ks, acc[i * NMT + j][e]);
+                        if (kbase + de < a.K) {
+                            const float v = acc[i * NMT + j][e];
+                            __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(v, yrsrc, voff, de * PQ4, 0);
+                        }
                     });
                 } else {
                     static_for<16>([&](auto E) WPK_LAMBDA {

@@ -68,21 +68,19 @@ struct Problem {
 int make_problem(const wpk_conv_desc *d, Problem *out);  // WPK_OK or a WPK_E_* code
 std::string desc_key(const wpk_conv_desc *d);
 
-// Division of a 31-bit number by a launch constant as a multiply and a shift (the divisor's
-// multiplier is computed on the host): q = mulhi(n, mul) >> sh for d > 1.  With L = ceil(log2 d)
-// and mul = ceil(2^(31+L) / d), mul fits 32 bits and the quotient is exact for every n < 2^31.
+// Division of a 31-bit number by a launch constant as a multiply, an add and a shift (the
+// divisor's multiplier is computed on the host): with L = ceil(log2 d) and
+// mul = floor(2^32 * (2^L - d) / d) + 1, q = (mulhi(n, mul) + n) >> L is exact for every
+// n < 2^31 and every d >= 1 (d = 1 and powers of two give mul = 1, which adds nothing), and the
+// sum cannot overflow 32 bits because mulhi(n, mul) <= n.
 struct FastDiv {
-    uint32_t mul, sh, d;
+    uint32_t mul, sh;
 };
 inline FastDiv make_fastdiv(uint32_t d)
 {
-    FastDiv f = {0, 0, d};
-    if (d > 1) {
-        uint32_t L = 0;
-        while ((1ull << L) < d) ++L;
-        f.mul = (uint32_t)((((uint64_t)1 << (31 + L)) + d - 1) / d);
-        f.sh = L - 1;
-    }
+    uint32_t L = 0;
+    while ((1ull << L) < d) ++L;
+    FastDiv f = {(uint32_t)((((uint64_t)1 << 32) * ((1ull << L) - d)) / d + 1), L};
     return f;
 }
 

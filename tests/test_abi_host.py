@@ -312,8 +312,8 @@ def test_workspace_slots_cover_every_sharer_of_a_tile():
 
 
 def test_fast_division_by_launch_constants(tmp_path):
-    """The kernels divide by launch constants with a host-computed multiplier and a shift; the
-    quotient must be exact for every dividend below 2^31.  Compiled from the library's own
+    """The kernels divide by launch constants with a host-computed multiplier, an add and a shift;
+    the quotient must be exact for every dividend below 2^31 and every divisor from 1 up.  Compiled from the library's own
     header and checked against the plain quotient: every small pair, then edge and random ones."""
     src = tmp_path / "fdiv.cpp"
     src.write_text(r'''
@@ -324,7 +324,7 @@ def test_fast_division_by_launch_constants(tmp_path):
 #include "wpk_internal.h"
 static uint32_t q(uint32_t n, const wpk::FastDiv &f)
 {
-    return f.d == 1 ? n : (uint32_t)(((uint64_t)n * f.mul) >> 32) >> f.sh;
+    return ((uint32_t)(((uint64_t)n * f.mul) >> 32) + n) >> f.sh;
 }
 int main()
 {
