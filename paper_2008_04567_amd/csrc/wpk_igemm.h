@@ -503,86 +503,95 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                 // is below y_bytes < 2^32
                 const unsigned voff = a.yl ? (unsigned)(((size_t)m * a.K + kbase) * 4)
                                            : (unsigned)((((size_t)n * a.K + kbase) * a.PQ + pq) * 4);
-                if (a.yl == 2 && !atomic) {
-                    // channels-last y with K a multiple of 4 and 16-byte aligned tensors: the four
-                    // registers 4g..4g+3 of a lane are four consecutive channels of its pixel
-                    const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
-                        (void *)(a.bias ? a.bias : a.y), 0, a.bias ? a.K * 4 : 0, 0x00020000);
-                    const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
-                        (void *)(a.res ? a.res : a.y), 0, a.res ? (int)a.y_bytes : 0, 0x00020000);
-                    v4f add[4];
-                    if (fused)
+                // A 32-channel block that lies wholly below K (the usual case) stores without a
+                // bound check per register; the check costs an exec-mask round trip each.
+                auto emit = [&](auto FULL) WPK_LAMBDA {
+                    constexpr bool full = decltype(FULL)::value;
+                    if (a.yl == 2 && !atomic) {
+                        // channels-last y with K a multiple of 4 and 16-byte aligned tensors: the four
+                        // registers 4g..4g+3 of a lane are four consecutive channels of its pixel
+                        const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
+                            (void *)(a.bias ? a.bias : a.y), 0, a.bias ? a.K * 4 : 0, 0x00020000);
+                        const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
+                            (void *)(a.res ? a.res : a.y), 0, a.res ? (int)a.y_bytes : 0, 0x00020000);
+                        v4f add[4];
+                        if (fused)
+                            static_for<4>([&](auto G) WPK_LAMBDA {
+                                constexpr int g = decltype(G)::value;
+                                v4f t = __builtin_bit_cast(
+                                    v4f, __builtin_amdgcn_raw_buffer_load_b128(brsrc, kbase * 4, 32 * g, 0));
+                                if (full || kbase + 8 * g < a.K)
+                                    t += __builtin_bit_cast(
+                                        v4f, __builtin_amdgcn_raw_buffer_load_b128(rrsrc, voff, 32 * g, 0));
+                                add[g] = t;
+                            });
                         static_for<4>([&](auto G) WPK_LAMBDA {
                             constexpr int g = decltype(G)::value;
-                            v4f t = __builtin_bit_cast(
-                                v4f, __builtin_amdgcn_raw_buffer_load_b128(brsrc, kbase * 4, 32 * g, 0));
-                            if (kbase + 8 * g < a.K)
-                                t += __builtin_bit_cast(
-                                    v4f, __builtin_amdgcn_raw_buffer_load_b128(rrsrc, voff, 32 * g, 0));
-                            add[g] = t;
-                        });
-                    static_for<4>([&](auto G) WPK_LAMBDA {
-                        constexpr int g = decltype(G)::value;
-                        if (kbase + 8 * g < a.K) {
-                            v4f v = {acc[i * NMT + j][4 * g], acc[i * NMT + j][4 * g + 1],
-                                     acc[i * NMT + j][4 * g + 2], acc[i * NMT + j][4 * g + 3]};
-                            if (fused) {
-                                v += add[g];
-                                if (a.relu)
-                                    v = (v4f){fmaxf(v[0], 0.0f), fmaxf(v[1], 0.0f), fmaxf(v[2], 0.0f),
-                                              fmaxf(v[3], 0.0f)};
+                            if (full || kbase + 8 * g < a.K) {
+                                v4f v = {acc[i * NMT + j][4 * g], acc[i * NMT + j][4 * g + 1],
+                                         acc[i * NMT + j][4 * g + 2], acc[i * NMT + j][4 * g + 3]};
+                                if (fused) {
+                                    v += add[g];
+                                    if (a.relu)
+                                        v = (v4f){fmaxf(v[0], 0.0f), fmaxf(v[1], 0.0f), fmaxf(v[2], 0.0f),
+                                                  fmaxf(v[3], 0.0f)};
+                                }
+                                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), yrsrc, voff,
+                                                                       32 * g, kYStorePolicy);
                             }
-                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), yrsrc, voff,
-                                                                   32 * g, kYStorePolicy);
-                        }
-                    });
-                } else if (fused) {
-                    const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
-                        (void *)(a.bias ? a.bias : a.y), 0, a.bias ? a.K * 4 : 0, 0x00020000);
-                    const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
-                        (void *)(a.res ? a.res : a.y), 0, a.res ? (int)a.y_bytes : 0, 0x00020000);
-                    // everything the 16 outputs of this block add is fetched first, so the loads
-                    // are all in flight together; then the stores
-                    float add[16];
-                    static_for<16>([&](auto E) WPK_LAMBDA {
-                        constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
-                        float t = __builtin_bit_cast(
-                            float, __builtin_amdgcn_raw_buffer_load_b32(brsrc, kbase * 4, de * 4, 0));
-                        if (kbase + de < a.K)
-                            t += __builtin_bit_cast(
-                                float, __builtin_amdgcn_raw_buffer_load_b32(rrsrc, voff, de * PQ4, 0));
-                        add[e] = t;
-                    });
-                    static_for<16>([&](auto E) WPK_LAMBDA {
-                        constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
-                        if (kbase + de < a.K) {
-                            float v = acc[i * NMT + j][e] + add[e];
-                            v = a.relu ? fmaxf(v, 0.0f) : v;
-                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
-                                                                  voff, de * PQ4, kYStorePolicy);
-                        }
-                    });
-                } else if (atomic) {
-                    // (no-return fp32 adds, addressed like the stores)
-                    static_for<16>([&](auto E) WPK_LAMBDA {
-                        constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
-                        if (kbase + de < a.K) {
-                            const float v = acc[i * NMT + j][e];
-                            __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(v, yrsrc, voff, de * PQ4, 0);
-                        }
-                    });
-                } else {
-                    static_for<16>([&](auto E) WPK_LAMBDA {
-                        constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
-                        if (kbase + de < a.K) {
-                            // a copy first: a bit cast taken straight from a vector element
-                            // reads element 0 with this compiler
-                            const float v = acc[i * NMT + j][e];
-                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
-                                                                  voff, de * PQ4, kYStorePolicy);
-                        }
-                    });
-                }
+                        });
+                    } else if (fused) {
+                        const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
+                            (void *)(a.bias ? a.bias : a.y), 0, a.bias ? a.K * 4 : 0, 0x00020000);
+                        const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
+                            (void *)(a.res ? a.res : a.y), 0, a.res ? (int)a.y_bytes : 0, 0x00020000);
+                        // everything the 16 outputs of this block add is fetched first, so the loads
+                        // are all in flight together; then the stores
+                        float add[16];
+                        static_for<16>([&](auto E) WPK_LAMBDA {
+                            constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
+                            float t = __builtin_bit_cast(
+                                float, __builtin_amdgcn_raw_buffer_load_b32(brsrc, kbase * 4, de * 4, 0));
+                            if (full || kbase + de < a.K)
+                                t += __builtin_bit_cast(
+                                    float, __builtin_amdgcn_raw_buffer_load_b32(rrsrc, voff, de * PQ4, 0));
+                            add[e] = t;
+                        });
+                        static_for<16>([&](auto E) WPK_LAMBDA {
+                            constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
+                            if (full || kbase + de < a.K) {
+                                float v = acc[i * NMT + j][e] + add[e];
+                                v = a.relu ? fmaxf(v, 0.0f) : v;
+                                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
+                                                                      voff, de * PQ4, kYStorePolicy);
+                            }
+                        });
+                    } else if (atomic) {
+                        // (no-return fp32 adds, addressed like the stores)
+                        static_for<16>([&](auto E) WPK_LAMBDA {
+                            constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
+                            if (full || kbase + de < a.K) {
+                                const float v = acc[i * NMT + j][e];
+                                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(v, yrsrc, voff, de * PQ4, 0);
+                            }
+                        });
+                    } else {
+                        static_for<16>([&](auto E) WPK_LAMBDA {
+                            constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
+                            if (full || kbase + de < a.K) {
+                                // a copy first: a bit cast taken straight from a vector element
+                                // reads element 0 with this compiler
+                                const float v = acc[i * NMT + j][e];
+                                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
+                                                                      voff, de * PQ4, kYStorePolicy);
+                            }
+                        });
+                    }
+                };
+                if (n0 + wave_n * TN + i * 32 + 32 <= a.K)
+                    emit(std::true_type{});
+                else
+                    emit(std::false_type{});
             });
         }
     });
