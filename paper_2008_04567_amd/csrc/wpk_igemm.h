@@ -172,13 +172,27 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
             xvoff[i] = a.xl ? ((n * a.H + p * a.stride_h) * a.W + q * a.stride_w) * a.C * 4
                             : ((n * a.C * a.H + p * a.stride_h) * a.W + q * a.stride_w) * 4;
             unsigned inv = 0x80000000u;
-            for (int r = 0; r < a.R; ++r) {
-                int ih = ih0 + r * a.dil_h;
-                if (ih < 0 || ih >= a.H) inv |= 1u << r;
+            // rows below the image are r < -ih0, rows past it r >= H - ih0 when the dilation is 1:
+            // two clamped shifts instead of a loop over the filter
+            auto outside = [](int o0, int len, int taps) WPK_LAMBDA {
+                const int lo = min(max(-o0, 0), taps), hi = min(max(len - o0, 0), taps);
+                return ((1u << lo) - 1u) | (((1u << taps) - 1u) & ~((1u << hi) - 1u));
+            };
+            if (a.dil_h == 1) {
+                inv |= outside(ih0, a.H, a.R);
+            } else {
+                for (int r = 0; r < a.R; ++r) {
+                    int ih = ih0 + r * a.dil_h;
+                    if (ih < 0 || ih >= a.H) inv |= 1u << r;
+                }
             }
-            for (int sx = 0; sx < a.S; ++sx) {
-                int iw = iw0 + sx * a.dil_w;
-                if (iw < 0 || iw >= a.W) inv |= 1u << (16 + sx);
+            if (a.dil_w == 1) {
+                inv |= outside(iw0, a.W, a.S) << 16;
+            } else {
+                for (int sx = 0; sx < a.S; ++sx) {
+                    int iw = iw0 + sx * a.dil_w;
+                    if (iw < 0 || iw >= a.W) inv |= 1u << (16 + sx);
+                }
             }
             xinv[i] = inv;
         }
