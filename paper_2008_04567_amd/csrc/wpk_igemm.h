@@ -72,7 +72,8 @@ __device__ __forceinline__ int fdiv(int n, const FastDiv &f)
     return (int)((__umulhi((unsigned)n, f.mul) + (unsigned)n) >> f.sh);
 }
 
-// Cache policy of the stores of y: sc0 | sc1, written through the per-XCD L2 as they are issued.
+// Cache policy of the stores of y in [N][K][P][Q] layout (whole 128-byte runs per half-wave):
+// sc0 | sc1, written through the per-XCD L2 as they are issued.
 // With the default policy the outputs sit dirty in the L2s until the kernel ends and are written
 // back then, before the next dispatch may start; nobody in this launch reads them again.  Measured:
 // 0.8 us per launch on a layer that writes 12.8 MB, nothing on small outputs.
@@ -519,8 +520,11 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                                            : (unsigned)((((size_t)n * a.K + kbase) * a.PQ + pq) * 4);
                 // A 32-channel block that lies wholly below K (the usual case) stores without a
                 // bound check per register; the check costs an exec-mask round trip each.
-                auto emit = [&](auto FULL) WPK_LAMBDA {
+                auto emit = [&](auto FULL, auto THROUGH) WPK_LAMBDA {
                     constexpr bool full = decltype(FULL)::value;
+                    // channels-last outputs leave a lane in 16-byte pieces that only the L2 merges
+                    // into whole lines: they keep the default write-back policy
+                    constexpr int policy = decltype(THROUGH)::value ? kYStorePolicy : 0;
                     if (a.yl == 2 && !atomic) {
                         // channels-last y with K a multiple of 4 and 16-byte aligned tensors: the four
                         // registers 4g..4g+3 of a lane are four consecutive channels of its pixel
@@ -551,7 +555,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                                                   fmaxf(v[3], 0.0f)};
                                 }
                                 __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), yrsrc, voff,
-                                                                       32 * g, kYStorePolicy);
+                                                                       32 * g, policy);
                             }
                         });
                     } else if (fused) {
@@ -577,7 +581,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                                 float v = acc[i * NMT + j][e] + add[e];
                                 v = a.relu ? fmaxf(v, 0.0f) : v;
                                 __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
-                                                                      voff, de * PQ4, kYStorePolicy);
+                                                                      voff, de * PQ4, policy);
                             }
                         });
                     } else if (atomic) {
@@ -597,15 +601,23 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                                 // reads element 0 with this compiler
                                 const float v = acc[i * NMT + j][e];
                                 __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
-                                                                      voff, de * PQ4, kYStorePolicy);
+                                                                      voff, de * PQ4, policy);
                             }
                         });
                     }
                 };
-                if (n0 + wave_n * TN + i * 32 + 32 <= a.K)
-                    emit(std::true_type{});
-                else
-                    emit(std::false_type{});
+                const bool whole = n0 + wave_n * TN + i * 32 + 32 <= a.K;
+                if (a.yl == 0) {
+                    if (whole)
+                        emit(std::true_type{}, std::true_type{});
+                    else
+                        emit(std::false_type{}, std::true_type{});
+                } else {
+                    if (whole)
+                        emit(std::true_type{}, std::false_type{});
+                    else
+                        emit(std::false_type{}, std::false_type{});
+                }
             });
         }
     });
