@@ -145,7 +145,8 @@ def main():
         # the timed region runs whole passes of a plan on separate buffers: outputs that a layer sums
         # into with atomics are zeroed once per pass, so candidates are timed without that launch
         opt = B.tune_default_options(mode=args.tune_mode, verbose=1 if args.verbose_tune else 0,
-                                     zero_ahead=0 if args.pipeline == 2 else 1)
+                                     zero_ahead=0 if args.pipeline == 2 else 1,
+                                     epilogue=1 if args.fused else 0)
         if args.refine is not None:
             opt.refine = args.refine
         seen = set()

@@ -183,6 +183,9 @@ typedef struct wpk_tune_options {
                              with the launch that zeroes y, as a single call pays it; 1 without it,
                              as in a plan run as whole passes, which zeroes such outputs once per pass
                              ahead of the layers (wpk_plan_run)                                   */
+    int32_t epilogue;     /* 1: candidates are timed with a rectifier as epilogue, for layers that will
+                             run with one (wpk_plan_set_epilogue): fused into the launch where the
+                             configuration allows, a pass of its own after atomics; 0 (default): none */
 } wpk_tune_options;
 
 /* Fill `o` with the defaults above. */

@@ -49,7 +49,7 @@ class TuneOptions(ctypes.Structure):
                 ("seed", ctypes.c_uint64), ("reps", ctypes.c_int32),
                 ("min_group_us", ctypes.c_double), ("mode", ctypes.c_int32),
                 ("verbose", ctypes.c_int32), ("refine", ctypes.c_int32),
-                ("zero_ahead", ctypes.c_int32)]
+                ("zero_ahead", ctypes.c_int32), ("epilogue", ctypes.c_int32)]
 
 
 class TuneReport(ctypes.Structure):

@@ -640,8 +640,9 @@ static int measure_us(TuneCtx &t, const wpk_conv_config &cfg, double *us_out, do
         WPK_HIP(hipEventRecord(t.e0, t.st));
         for (int i = 0; i < launches; ++i) {
             // (zero_ahead: y keeps accumulating from launch to launch, which costs the same time)
-            int r = run_config(t.pr, cfg, t.ktab, t.x, t.wp, t.y, &t.fix, t.st, Epilogue(),
-                               t.opt.zero_ahead != 0);
+            Epilogue epi;
+            epi.relu = t.opt.epilogue != 0;
+            int r = run_config(t.pr, cfg, t.ktab, t.x, t.wp, t.y, &t.fix, t.st, epi, t.opt.zero_ahead != 0);
             if (r != WPK_OK) return r;
         }
         WPK_HIP(hipEventRecord(t.e1, t.st));

@@ -625,6 +625,7 @@ void wpk_tune_default_options(wpk_tune_options *o)
     o->verbose = 0;
     o->refine = 2;
     o->zero_ahead = 0;
+    o->epilogue = 0;
 }
 
 int wpk_ga_search(int32_t n_genes, const int32_t *lo, const int32_t *hi,
