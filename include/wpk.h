@@ -174,7 +174,8 @@ typedef struct wpk_tune_options {
     double  min_group_us; /* each timed group is sized to last at least this long, default 200   */
     int32_t mode;         /* 0 genetic search, 1 random search (same budget), 2 exhaustive        */
     int32_t verbose;      /* 1: print one line per generation to stderr                          */
-    int32_t refine;       /* after a search (modes 0, 1): at most this many rounds of trying every
+    int32_t refine;       /* after a search (modes 0, 1): a few dozen rule-based candidates are
+                             timed beside the winner, then at most this many rounds of trying every
                              other value of one gene of the winner at a time, then the five
                              fastest candidates are timed again in groups of at least 4 ms
                              (clocks settled under load) and the fastest kept; not part of

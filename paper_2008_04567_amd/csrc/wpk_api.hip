@@ -1009,6 +1009,48 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int
                              best_genes, &best_f, &evals, nullptr, nullptr, nullptr, 0);
     }
     if (t.opt.mode != 2 && t.opt.refine > 0 && best_f > 0.0 && !t.hip_failed && gens >= 0) {
+        // rule-based candidates beside the search's winner: the tile shapes that exhaustive
+        // searches over the workloads' layers put on top most often, each with the persistent
+        // schedules and with reductions split to about 3.5 workgroups per compute unit
+        {
+            static const int32_t kShapes[][6] = {{64, 64, 16, 2, 2, 2},  {64, 64, 32, 2, 2, 2}, {64, 128, 16, 2, 2, 2},
+                                                 {128, 64, 16, 2, 2, 2}, {64, 64, 32, 2, 2, 1}, {128, 64, 32, 4, 2, 2}};
+            auto consider = [&](const wpk_conv_config &c) {
+                int32_t g[WPK_N_GENES];
+                if (wpk_config_to_genes(&c, g) != WPK_OK || !tune_constraint(g, WPK_N_GENES, &t) ||
+                    t.times_us.count(wpk_config_id(&c)))
+                    return;
+                double f = tune_fitness(g, WPK_N_GENES, &t);
+                ++evals;
+                if (f > best_f) {
+                    best_f = f;
+                    memcpy(best_genes, g, sizeof g);
+                }
+            };
+            const int cus = g_cus > 0 ? g_cus : 256;
+            for (const auto &sh : kShapes) {
+                wpk_conv_config c = {sh[0], sh[1], sh[2], sh[3], sh[4], 1, 0, 0, sh[5], 0};
+                for (int p = 2; p <= 4; ++p) {
+                    c.persist = p;
+                    consider(c);
+                }
+                c.persist = 0;
+                c.xcd_remap = 1;
+                int64_t tiles = ((pr.M + c.bm - 1) / c.bm) * ((pr.d.k + c.bn - 1) / c.bn);
+                int want = (int)std::max<int64_t>(1, (7 * (int64_t)cus / 2 + tiles / 2) / tiles);
+                for (int i = 0; i < kGeneCounts[5]; ++i) {
+                    int sk = kSplitVals[i];
+                    if (sk < want - 1 || sk > want + 2) continue;
+                    c.split_k = sk;
+                    c.reduce = 0;
+                    consider(c);
+                    if (sk > 1) {
+                        c.reduce = 1;
+                        consider(c);
+                    }
+                }
+            }
+        }
         // one gene of the winner at a time, every other value of it
         for (int round = 0; round < t.opt.refine; ++round) {
             bool moved = false;
