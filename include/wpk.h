@@ -183,7 +183,8 @@ typedef struct wpk_tune_options {
     int32_t zero_ahead;   /* how candidates that accumulate into y with atomics are timed: 0 (default)
                              with the launch that zeroes y, as a single call pays it; 1 without it,
                              as in a plan run as whole passes, which zeroes such outputs once per pass
-                             ahead of the layers (wpk_plan_run)                                   */
+                             ahead of the layers (wpk_plan_run); the candidate is charged its share of
+                             that launch at 3 TB/s instead                                        */
     int32_t epilogue;     /* 1: candidates are timed with a rectifier as epilogue, for layers that will
                              run with one (wpk_plan_set_epilogue): fused into the launch where the
                              configuration allows, a pass of its own after atomics; 0 (default): none */

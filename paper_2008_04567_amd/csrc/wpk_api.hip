@@ -665,6 +665,9 @@ static int measure_us(TuneCtx &t, const wpk_conv_config &cfg, double *us_out, do
     }
     std::sort(samples.begin(), samples.end());
     *us_out = samples[samples.size() / 2];
+    // zero_ahead leaves the zeroing of y out of the launches; its share of the one zeroing launch
+    // per pass is charged at 3 TB/s
+    if (t.opt.zero_ahead && zeroes_all_of_y(t.pr, cfg, &t.fix)) *us_out += (double)t.pr.y_elems * 4.0 / 3.0e6;
     return WPK_OK;
 }
 
@@ -1032,9 +1035,13 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int
                 wpk_conv_config c = {sh[0], sh[1], sh[2], sh[3], sh[4], 1, 0, 0, sh[5], 0};
                 for (int p = 2; p <= 4; ++p) {
                     c.persist = p;
+                    c.reduce = 0;
+                    consider(c);
+                    c.reduce = 1;
                     consider(c);
                 }
                 c.persist = 0;
+                c.reduce = 0;
                 c.xcd_remap = 1;
                 int64_t tiles = ((pr.M + c.bm - 1) / c.bm) * ((pr.d.k + c.bn - 1) / c.bn);
                 int want = (int)std::max<int64_t>(1, (7 * (int64_t)cus / 2 + tiles / 2) / tiles);
