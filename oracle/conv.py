@@ -109,33 +109,6 @@ def conv2d_sampled(shape, x, w, flat_idx):
     return y, d
 
 
-def conv2d_fused(shape, x, w, bias=None, residual=None, relu=False, threads=0):
-    """The fused operator of Section 2.1 (operator fusion: the sub-graph convolution -> per-channel
-    bias -> element-wise addition of a second tensor -> rectifier computed as one operator), written
-    out as its definition on top of the seven-loop convolution:
-
-        z[n][k][p][q] = conv(x, w)[n][k][p][q] + bias[k] + residual[n][k][p][q]
-        y = max(z, 0) if relu else z
-
-    all in fp64; absent terms are zero.  Returns ``(y64, dnorm)`` where dnorm adds |bias| and
-    |residual| to the convolution's normaliser: the sum of the magnitudes of everything added
-    into an output, which bounds the rounding error of any summation order (the rectifier does
-    not increase a difference)."""
-    y, d, _ = conv2d(shape, x, w, threads=threads)
-    if bias is not None:
-        b = np.asarray(bias, dtype=np.float32).astype(np.float64)
-        assert b.shape == (shape.k,), "bias has one entry per output channel"
-        y = y + b[None, :, None, None]
-        d = d + np.abs(b)[None, :, None, None]
-    if residual is not None:
-        r = np.asarray(residual, dtype=np.float32).astype(np.float64).reshape(y.shape)
-        y = y + r
-        d = d + np.abs(r)
-    if relu:
-        y = np.where(y > 0.0, y, 0.0)
-    return y, d
-
-
 LAYOUTS = ("NCHW", "NHWC")
 
 
@@ -153,4 +126,35 @@ def conv2d_layout(shape, x, w, x_layout="NCHW", y_layout="NCHW", threads=0):
     y, d, _ = conv2d(shape, np.ascontiguousarray(x), w, threads=threads)
     if y_layout == "NHWC":
         y, d = (np.ascontiguousarray(t.transpose(0, 2, 3, 1)) for t in (y, d))
+    return y, d
+
+
+def conv2d_fused(shape, x, w, bias=None, residual=None, relu=False, threads=0,
+                 x_layout="NCHW", y_layout="NCHW"):
+    """The fused operator of Section 2.1 (operator fusion: the sub-graph convolution -> per-channel
+    bias -> element-wise addition of a second tensor -> rectifier computed as one operator), written
+    out as its definition on top of the seven-loop convolution:
+
+        z[n][k][p][q] = conv(x, w)[n][k][p][q] + bias[k] + residual[n][k][p][q]
+        y = max(z, 0) if relu else z
+
+    all in fp64; absent terms are zero.  ``x`` is stored as ``x_layout`` says; the result and the
+    residual are stored as ``y_layout`` says ([N][K][P][Q] or channels-last [N][P][Q][K]), so the
+    bias runs along axis 1 or along the last axis.  Returns ``(y64, dnorm)`` where dnorm adds |bias|
+    and |residual| to the convolution's normaliser: the sum of the magnitudes of everything added
+    into an output, which bounds the rounding error of any summation order (the rectifier does
+    not increase a difference)."""
+    y, d = conv2d_layout(shape, x, w, x_layout, y_layout, threads=threads)
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float32).astype(np.float64)
+        assert b.shape == (shape.k,), "bias has one entry per output channel"
+        along = (1, shape.k, 1, 1) if y_layout == "NCHW" else (1, 1, 1, shape.k)
+        y = y + b.reshape(along)
+        d = d + np.abs(b).reshape(along)
+    if residual is not None:
+        r = np.asarray(residual, dtype=np.float32).astype(np.float64).reshape(y.shape)
+        y = y + r
+        d = d + np.abs(r)
+    if relu:
+        y = np.where(y > 0.0, y, 0.0)
     return y, d

@@ -10,6 +10,13 @@ from paper_2008_04567_amd import binding as B
 from paper_2008_04567_amd import workloads as W
 
 TOL = 1e-4
+# Regression guard beside the pass bar.  An honest fp32 kernel lands far inside TOL: the largest
+# normalised error ever recorded over this suite is 3e-6 (a 4608-term reduction summed in slices).
+# A mistake worth a single dropped or doubled term is about 1/L of D on the outputs it touches,
+# 2e-4 for the longest reduction here but diluted below TOL on outputs where that term is small,
+# so a tenfold margin over the recorded worst is asserted as well.
+RECORDED_WORST = 3e-6
+GUARD = 10 * RECORDED_WORST
 
 
 def torch_dev():
@@ -37,6 +44,8 @@ def assert_close(y_gpu, y_ref, d_ref, what=""):
     err = np.abs(y_gpu - y_ref) / np.where(zero, 1.0, d_ref)
     worst = float(err.max()) if err.size else 0.0
     assert worst <= TOL, "%s: max normalised error %.3g > %g" % (what, worst, TOL)
+    assert worst <= GUARD, ("%s: max normalised error %.3g is inside the tolerance but above %g, ten times "
+                            "the worst this suite has recorded" % (what, worst, GUARD))
     return worst
 
 
@@ -106,17 +115,8 @@ def check_layout(layer, layout, cfg=None, bias=None, residual=None, relu=False, 
     if residual is not None:    # given as [N][K][P][Q]
         res_host = np.ascontiguousarray(residual.transpose(0, 2, 3, 1)) if yl == "NHWC" else residual
     sh = oc.shape_from_layer(layer)
-    y_ref, d_ref = oc.conv2d_layout(sh, x_host, w, xl, yl)
-    if bias is not None or residual is not None or relu:
-        b64 = np.zeros(layer["k"]) if bias is None else bias.astype(np.float64)
-        bshape = (1, 1, 1, -1) if yl == "NHWC" else (1, -1, 1, 1)
-        y_ref = y_ref + b64.reshape(bshape)
-        d_ref = d_ref + np.abs(b64).reshape(bshape)
-        if res_host is not None:
-            y_ref = y_ref + res_host.astype(np.float64)
-            d_ref = d_ref + np.abs(res_host.astype(np.float64))
-        if relu:
-            y_ref = np.maximum(y_ref, 0.0)
+    y_ref, d_ref = oc.conv2d_fused(sh, x_host, w, bias=bias, residual=res_host, relu=relu,
+                                   x_layout=xl, y_layout=yl)
     n_out = y_ref.size
     guard = 256
     buf = torch.full((n_out + 2 * guard,), 12345.0, device=dev, dtype=torch.float32)

@@ -436,3 +436,44 @@ def test_channels_last_delta_and_channel_order():
     perm = np.array([3, 0, 5, 1, 4, 2])
     y, _ = oc.conv2d_layout(sh, x, eye[perm], "NHWC", "NHWC")
     assert np.array_equal(y, x[..., perm].astype(np.float64))
+
+
+@pytest.mark.parametrize("cfg", [
+    (2, 3, 5, 4, 2, 3, 2, (1, 1), (1, 0), (1, 1)),
+    (1, 4, 6, 5, 3, 2, 3, (2, 1), (0, 2), (1, 2)),
+])
+def test_fused_channels_last_against_flat_evaluator(cfg):
+    """The fused operator with channels-last tensors, against an evaluator that works on flat
+    buffers: output element i of [N][P][Q][K] gets bias[i mod K] and the residual's element i."""
+    n_, c_, h_, w_, k_, r_, s_, st, pd, dl = cfg
+    rng = np.random.default_rng(77 + c_)
+    x = rng.uniform(-1, 1, (n_, h_, w_, c_)).astype(np.float32)
+    w = rng.uniform(-1, 1, (k_, c_, r_, s_)).astype(np.float32)
+    b = rng.uniform(-1, 1, k_).astype(np.float32)
+    conv = _brute_nhwc(n_, c_, h_, w_, k_, r_, s_, st, pd, dl, x, w)
+    res = rng.uniform(-1, 1, conv.shape).astype(np.float32)
+    flat = conv.ravel().copy()
+    for i in range(flat.size):
+        flat[i] += float(b[i % k_]) + float(res.ravel()[i])
+        flat[i] = flat[i] if flat[i] > 0.0 else 0.0
+    sh = oc.make_shape(n_, c_, h_, w_, k_, r_, s_, st, pd, dl)
+    y, d = oc.conv2d_fused(sh, x, w, bias=b, residual=res, relu=True, x_layout="NHWC", y_layout="NHWC")
+    assert y.shape == conv.shape and (y == 0).any() and (y > 0).any()
+    assert np.max(np.abs(y.ravel() - flat)) <= 1e-12 * max(1.0, d.max())
+    # the normaliser: the convolution's, plus |bias| along the LAST axis, plus |residual|
+    _, d0 = oc.conv2d_layout(sh, x, w, "NHWC", "NHWC")
+    assert np.array_equal(d, d0 + np.abs(b.astype(np.float64)) + np.abs(res.astype(np.float64)))
+    # mixed layouts: x in one layout, y and the residual in the other -- same values, permuted
+    y2, d2 = oc.conv2d_fused(sh, x, w, bias=b, residual=res.transpose(0, 3, 1, 2), relu=True,
+                             x_layout="NHWC", y_layout="NCHW")
+    assert np.array_equal(y2, y.transpose(0, 3, 1, 2)) and np.array_equal(d2, d.transpose(0, 3, 1, 2))
+    y3, _ = oc.conv2d_fused(sh, x.transpose(0, 3, 1, 2), w, bias=b, residual=res, relu=True,
+                            x_layout="NCHW", y_layout="NHWC")
+    assert np.array_equal(y3, y)
+    # a one-hot bias changes one index of the last axis only
+    onehot = np.zeros(k_, np.float32)
+    onehot[1] = 3.0
+    y4, _ = oc.conv2d_fused(sh, x, w, bias=onehot, x_layout="NHWC", y_layout="NHWC")
+    y5, _ = oc.conv2d_layout(sh, x, w, "NHWC", "NHWC")
+    diff = y4 - y5
+    assert np.allclose(diff[..., 1], 3.0, rtol=0, atol=1e-12) and np.all(np.delete(diff, 1, axis=3) == 0.0)
