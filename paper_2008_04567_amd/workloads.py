@@ -83,6 +83,11 @@ def config4(n=16):
             layer("cfg4.3x3s2_128_128_56", n, 128, 56, 128, 3, 2, 1, seed=4003)]
 
 
+# Feature-map edge in each of the four residual stages of an ImageNet ResNet (224x224 input): the
+# sizes are data of the workload, listed, not computed from strides.
+STAGE_HW = (56, 28, 14, 7)
+
+
 def resnet50_stack(n=1):
     """Config 5: every convolution of a ResNet-50 v1 bottleneck network, in network order.
 
@@ -91,19 +96,21 @@ def resnet50_stack(n=1):
     stride 2; the first block of every stage has a 1x1 projection shortcut with the block's
     stride.  53 layers; each gets its own seed."""
     out = [layer("stem", n, 3, 224, 64, 7, 2, 3, x_dist="u11", seed=5000)]
-    cin, hw, idx = 64, 56, 1
+    cin, idx = 64, 1
     for stage, (blocks, width) in enumerate(zip([3, 4, 6, 3], [64, 128, 256, 512])):
         for b in range(blocks):
             stride = 2 if (b == 0 and stage > 0) else 1
+            # feature-map sizes written out: what the block receives, what its strided layers emit
+            hw_out = STAGE_HW[stage]
+            hw = STAGE_HW[stage - 1] if stride == 2 else hw_out
             tag = "s%db%d" % (stage + 1, b)
             out.append(layer(tag + ".c1", n, cin, hw, width, 1, 1, 0, seed=5000 + idx)); idx += 1
             out.append(layer(tag + ".c2", n, width, hw, width, 3, stride, 1, seed=5000 + idx)); idx += 1
-            hw_out = hw // stride
             out.append(layer(tag + ".c3", n, width, hw_out, 4 * width, 1, 1, 0, seed=5000 + idx)); idx += 1
             if b == 0:
                 out.append(layer(tag + ".proj", n, cin, hw, 4 * width, 1, stride, 0,
                                  seed=5000 + idx)); idx += 1
-            cin, hw = 4 * width, hw_out
+            cin = 4 * width
     return out
 
 
@@ -122,17 +129,18 @@ def resnet18_stack(n=1):
     layers with widths 64/128/256/512; the first 3x3 of stages 2-4 has stride 2 and that block
     has a 1x1 stride-2 projection shortcut.  20 layers."""
     out = [layer("stem", n, 3, 224, 64, 7, 2, 3, x_dist="u11", seed=7000)]
-    cin, hw, idx = 64, 56, 1
+    cin, idx = 64, 1
     for stage, width in enumerate([64, 128, 256, 512]):
         for b in range(2):
             stride = 2 if (b == 0 and stage > 0) else 1
+            hw_out = STAGE_HW[stage]
+            hw = STAGE_HW[stage - 1] if stride == 2 else hw_out
             tag = "s%db%d" % (stage + 1, b)
             out.append(layer(tag + ".c1", n, cin, hw, width, 3, stride, 1, seed=7000 + idx)); idx += 1
-            hw_out = hw // stride
             out.append(layer(tag + ".c2", n, width, hw_out, width, 3, 1, 1, seed=7000 + idx)); idx += 1
             if stride == 2:
                 out.append(layer(tag + ".proj", n, cin, hw, width, 1, 2, 0, seed=7000 + idx)); idx += 1
-            cin, hw = width, hw_out
+            cin = width
     return out
 
 
