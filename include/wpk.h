@@ -16,7 +16,14 @@
  *     layout says so), at least 4-byte aligned.  y is overwritten in full (no accumulate).  x
  *     and y must not overlap.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued
- *     on it and the call returns without synchronising, unless stated otherwise.
+ *     on it and the call returns without synchronising, unless stated otherwise.  The one-shot
+ *     entry points (wpk_conv2d_fwd, _fwd_config, _fwd_fused, _fwd_fused_config) keep library
+ *     scratch that grows on demand: the first call with a new descriptor allocates its lookup
+ *     table, and a call that needs more packed-weight or workspace room than any call before it
+ *     frees and re-allocates that scratch, which synchronises the device.  Such a call must not be
+ *     recorded by a stream capture; calls after it with the same shapes only enqueue launches.
+ *     They serialise on one process-wide lock while they enqueue.  Plans allocate at build time
+ *     only.
  *   - Descriptors and config structs are HOST memory, copied by value during the call.
  *   - Return value: 0 (WPK_OK) or a negative WPK_E_* code; functions that return an id return
  *     it as a non-negative int.  Nothing throws or aborts across this boundary.
@@ -201,7 +208,13 @@ typedef struct wpk_tune_report {
     int32_t generations;
     int32_t rejected;      /* candidates that failed verification against wpk_conv2d_ref        */
     double seconds;        /* wall time of the search                                            */
+    int32_t stage;         /* which stage found `best`: WPK_STAGE_SEARCH (the search of Section 2.3
+                              itself), _RULE (a rule-based candidate), _REFINE (one gene of the winner
+                              varied), _DEFAULT (nothing beat wpk_config_default); the last three are
+                              the additions `refine` switches on                                  */
+    double search_us;      /* runtime of the best chromosome of the search alone, as the search timed it */
 } wpk_tune_report;
+enum { WPK_STAGE_SEARCH = 0, WPK_STAGE_RULE = 1, WPK_STAGE_REFINE = 2, WPK_STAGE_DEFAULT = 3 };
 
 /*
  * Search the kernel family for `d` on the current device with synthetic operands the library
@@ -273,8 +286,13 @@ int wpk_plan_run_layer(wpk_plan *plan, int32_t layer, const float *x, float *y, 
  * so the results are those of the unsplit plan whatever the layers feed each other; what it buys
  * is that the ramp, the meeting of shared tiles and the drain of one chain's launches hide
  * behind the other chain's arithmetic (about 6 % on a 53-layer stack at N = 16; it does not pay
- * for passes of a few layers).  Each half uses the cached configuration of its own descriptor
- * (batch n/2) if there is one, else the default.  WPK_E_UNSUPPORTED if a layer has batch 1.
+ * for passes of a few layers).  The two chains are not ordered against each other inside a pass,
+ * so a pass is split only when nothing one chain writes overlaps anything the other chain reads or
+ * writes at any layer (checked from the pointers of each wpk_plan_run(_fused) call: buffers reused
+ * in turns by tensors of different per-image size fail it); a pass that fails the check runs as one
+ * chain, with the same results.  Each half uses the cached configuration of its own descriptor
+ * (batch n/2) if there is one, else the default; wpk_plan_set_layer_config also applies to the
+ * halves where the configuration is legal for them.  WPK_E_UNSUPPORTED if a layer has batch 1.
  * Synchronises the device. */
 int wpk_plan_set_pipeline(wpk_plan *plan, int32_t ways);
 

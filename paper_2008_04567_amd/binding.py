@@ -55,7 +55,14 @@ class TuneOptions(ctypes.Structure):
 class TuneReport(ctypes.Structure):
     _fields_ = [("best", ConvConfig), ("best_us", ctypes.c_double), ("default_us", ctypes.c_double),
                 ("evaluations", ctypes.c_int32), ("generations", ctypes.c_int32),
-                ("rejected", ctypes.c_int32), ("seconds", ctypes.c_double)]
+                ("rejected", ctypes.c_int32), ("seconds", ctypes.c_double),
+                ("stage", ctypes.c_int32), ("search_us", ctypes.c_double)]
+
+    STAGE_NAMES = ("search", "rule", "refine", "default")
+
+    @property
+    def stage_name(self):
+        return self.STAGE_NAMES[self.stage] if 0 <= self.stage < 4 else "?"
 
 
 GA_CONSTRAINT_FN = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32,

@@ -1,6 +1,7 @@
 """Build libwpk.so (HIP, gfx950 only) in-tree with hipcc.
 
-``python -m paper_2008_04567_amd.build`` or ``build_library()``.  Translation units are compiled
+``python -m paper_2008_04567_amd.build`` (add ``--changed`` to compile only what is stale) or
+``build_library()``.  Translation units are compiled
 in parallel: the host part, the API/dispatch part and eight instantiation parts of the tiled
 kernel family.  Works without a GPU (hipcc cross-compiles).
 """
@@ -47,27 +48,44 @@ def sources_newer_than_lib():
     return any(os.path.getmtime(f) > t for f in files)
 
 
+def _stale(obj, deps):
+    if not os.path.exists(obj):
+        return True
+    t = os.path.getmtime(obj)
+    return any(os.path.getmtime(f) > t for f in deps)
+
+
 def build_library(force=True, verbose=False):
-    """Compile and link libwpk.so.  Returns its path."""
+    """Compile and link libwpk.so.  Returns its path.  With ``force=False`` only the objects whose
+    sources (or headers) are newer than they are get compiled again."""
     if not force and not sources_newer_than_lib():
         return LIB
     os.makedirs(OBJ, exist_ok=True)
     hipcc = _hipcc()
-    jobs = []
-    jobs.append([hipcc] + COMMON + ["-c", os.path.join(CSRC, "wpk_host.cpp"),
-                                    "-o", os.path.join(OBJ, "wpk_host.o")])
-    jobs.append([hipcc] + COMMON + DEVICE + ["-c", os.path.join(CSRC, "wpk_api.hip"),
-                                             "-o", os.path.join(OBJ, "wpk_api.o")])
+    src = lambda f: os.path.join(CSRC, f)
+    headers = [os.path.join(INCLUDE, "wpk.h"), src("wpk_internal.h")]
+    kernel_headers = headers + [src("wpk_igemm.h"), src("wpk_variants.def")]
+    jobs, objs = [], []
+
+    def add(cmd, deps):
+        objs.append(cmd[-1])
+        if force or _stale(cmd[-1], deps):
+            jobs.append(cmd)
+
+    add([hipcc] + COMMON + ["-c", src("wpk_host.cpp"), "-o", os.path.join(OBJ, "wpk_host.o")],
+        headers + [src("wpk_host.cpp"), src("wpk_variants.def")])
+    add([hipcc] + COMMON + DEVICE + ["-c", src("wpk_api.hip"), "-o", os.path.join(OBJ, "wpk_api.o")],
+        kernel_headers + [src("wpk_api.hip")])
     for part in range(N_PARTS):
-        jobs.append([hipcc] + COMMON + DEVICE + ["-DWPK_PART=%d" % part, "-c",
-                                                 os.path.join(CSRC, "wpk_igemm_inst.hip"),
-                                                 "-o", os.path.join(OBJ, "wpk_igemm_%d.o" % part)])
-    workers = min(len(jobs), max(1, (os.cpu_count() or 4)), 16)
-    with concurrent.futures.ThreadPoolExecutor(workers) as ex:
-        for out in ex.map(_run, jobs):
-            if verbose and out.strip():
-                print(out)
-    objs = [j[-1] for j in jobs]
+        add([hipcc] + COMMON + DEVICE + ["-DWPK_PART=%d" % part, "-c", src("wpk_igemm_inst.hip"),
+                                         "-o", os.path.join(OBJ, "wpk_igemm_%d.o" % part)],
+            kernel_headers + [src("wpk_igemm_inst.hip")])
+    if jobs:
+        workers = min(len(jobs), max(1, (os.cpu_count() or 4)), 16)
+        with concurrent.futures.ThreadPoolExecutor(workers) as ex:
+            for out in ex.map(_run, jobs):
+                if verbose and out.strip():
+                    print(out)
     _run(_link_command(objs))
     return LIB
 
@@ -102,4 +120,4 @@ def _link_command(objs):
 
 
 if __name__ == "__main__":
-    print(build_library(force=True, verbose="-v" in sys.argv))
+    print(build_library(force="--changed" not in sys.argv, verbose="-v" in sys.argv))

@@ -150,6 +150,13 @@ __global__ void epilogue_kernel(float *__restrict__ y, const float *__restrict__
     }
 }
 
+__global__ void fill_value_kernel(float *__restrict__ p, long long n, float v)
+{
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (long long)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
 // Synthetic operands for the tuner: value = lo + (hi-lo) * hash(index, seed) / 2^24.
 __global__ void fill_hash_kernel(float *__restrict__ p, long long n, unsigned seed, float lo, float hi)
 {
@@ -278,61 +285,87 @@ static int ensure_device()
 //    bias = (pad_h*W + pad_w)*4 keeps it non-negative; the kernel adds c0*H*W*4.
 //  - Three tail tables [32 rows], for K-steps of 8, 16 and 32: the rows from the start of the last
 //    step of the reduction, with absolute offsets; rows past C*R*S point at the always-set bit 31.
-// Layout of the upload: periodic | tail(8) | tail(16) | tail(32).
-static std::vector<int32_t> build_tap_tables(const Problem &pr)
+// Layout: periodic | tail(8) | tail(16) | tail(32).
+// Channels-last in channel quads (quad != 0): one entry per filter tap instead, {byte offset of the
+// tap (biased like the descriptor base), mask bits}, padded with zero entries to 32.
+// The tables are written on the device (one lane per entry) so that preparing a descriptor is a
+// launch on the caller's stream and nothing else: no host-to-device copy, no synchronisation.
+struct TapGeom {
+    int32_t R, S, W, C, CRS;
+    int32_t pad_h, pad_w, dil_h, dil_w;
+    int32_t cs, ps;   // element strides of x between channels / between pixels of a row
+    int32_t quad;
+    int32_t entries;
+};
+static TapGeom tap_geometry(const Problem &pr)
 {
     const wpk_conv_desc &d = pr.d;
+    TapGeom g;
+    g.R = d.r; g.S = d.s; g.W = d.w; g.C = d.c; g.CRS = pr.CRS;
+    g.pad_h = d.pad_h; g.pad_w = d.pad_w; g.dil_h = d.dil_h; g.dil_w = d.dil_w;
+    g.cs = pr.xl ? 1 : d.h * d.w;
+    g.ps = pr.xl ? d.c : 1;
+    g.quad = pr.xquad ? 1 : 0;
     const int RS = d.r * d.s;
-    if (pr.xquad) {
-        // channels-last in channel quads: one entry per filter tap, {byte offset of the tap (biased like the
-        // descriptor base), mask bit of r | mask bit of s << 8}; padded to 32 entries
-        const int biasl = (d.pad_h * d.w + d.pad_w) * d.c * 4;
-        std::vector<int32_t> t((size_t)std::max(RS, 32) * 2, 0);
-        for (int rs = 0; rs < RS; ++rs) {
-            int r = rs / d.s, s = rs % d.s;
-            t[2 * rs] = ((r * d.dil_h - d.pad_h) * d.w + s * d.dil_w - d.pad_w) * d.c * 4 + biasl;
-            t[2 * rs + 1] = r | (16 + s) << 8;
+    g.entries = pr.xquad ? std::max(RS, 32) : (RS + 3) * 32;
+    return g;
+}
+static size_t tap_table_bytes(const Problem &pr) { return (size_t)tap_geometry(pr).entries * 2 * sizeof(int32_t); }
+
+__global__ void __launch_bounds__(256) tap_table_kernel(int32_t *__restrict__ t, const TapGeom g)
+{
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= g.entries) return;
+    const int RS = g.R * g.S;
+    int off = 0, bits = 0;
+    if (g.quad) {
+        if (e < RS) {
+            const int r = e / g.S, s = e - r * g.S;
+            // ((r*dil_h - pad_h)*W + s*dil_w - pad_w)*C*4 plus the bias (pad_h*W + pad_w)*C*4
+            off = (r * g.dil_h * g.W + s * g.dil_w) * g.C * 4;
+            bits = r | (16 + s) << 8;
         }
-        return t;
-    }
-    // element strides of x: between channels, between pixels of a row (channels-last: 1 and C)
-    const int cs = pr.xl ? 1 : d.h * d.w, ps = pr.xl ? d.c : 1;
-    const int bias = (d.pad_h * d.w + d.pad_w) * ps * 4;
-    auto entry = [&](int c, int rs, int32_t *e) {
-        int r = rs / d.s, s = rs % d.s;
-        e[0] = (c * cs + ((r * d.dil_h - d.pad_h) * d.w + s * d.dil_w - d.pad_w) * ps) * 4 + bias;
-        e[1] = r | (16 + s) << 8;
-    };
-    std::vector<int32_t> t((size_t)(RS + 3) * 32 * 2, 0);
-    for (int ph = 0; ph < RS; ++ph)
-        for (int j = 0; j < 32; ++j) entry((ph + j) / RS, (ph + j) % RS, &t[((size_t)ph * 32 + j) * 2]);
-    const int bks[3] = {8, 16, 32};
-    for (int b = 0; b < 3; ++b) {
-        int k0 = (pr.CRS + bks[b] - 1) / bks[b] * bks[b] - bks[b];  // start of the last step
-        for (int j = 0; j < 32; ++j) {
-            int32_t *e = &t[((size_t)(RS + b) * 32 + j) * 2];
-            int kk = k0 + j;
-            if (kk < pr.CRS) {
-                entry(kk / RS, kk % RS, e);
-            } else {
-                e[0] = 0;
-                e[1] = kPadTapBit | kPadTapBit << 8;
-            }
+    } else {
+        const int table = e >> 5, j = e & 31;
+        int kk;          // reduction row relative to the step's channel base, or absolute (tails)
+        bool pad = false;
+        if (table < RS) {
+            kk = table + j;
+        } else {
+            const int bk = 8 << (table - RS);
+            kk = (g.CRS + bk - 1) / bk * bk - bk + j;
+            pad = kk >= g.CRS;
+        }
+        if (pad) {
+            bits = kPadTapBit | kPadTapBit << 8;
+        } else {
+            const int c = kk / RS, rs = kk - c * RS, r = rs / g.S, s = rs - r * g.S;
+            // (c*cs + ((r*dil_h - pad_h)*W + s*dil_w - pad_w)*ps)*4 plus the bias (pad_h*W + pad_w)*ps*4
+            off = (c * g.cs + (r * g.dil_h * g.W + s * g.dil_w) * g.ps) * 4;
+            bits = r | (16 + s) << 8;
         }
     }
-    return t;
+    t[2 * e] = off;
+    t[2 * e + 1] = bits;
 }
 
-static int upload_tap_table(const Problem &pr, int32_t **out)
+static int write_tap_table(const Problem &pr, int32_t *dptr, hipStream_t st)
 {
-    std::vector<int32_t> t = build_tap_tables(pr);
+    const TapGeom g = tap_geometry(pr);
+    hipLaunchKernelGGL(tap_table_kernel, dim3((g.entries + 255) / 256), dim3(256), 0, st, dptr, g);
+    WPK_HIP(hipGetLastError());
+    return WPK_OK;
+}
+
+// A table in memory of its own, ready when `st` reaches this point.
+static int upload_tap_table(const Problem &pr, int32_t **out, hipStream_t st)
+{
     int32_t *dptr = nullptr;
-    WPK_HIP(hipMalloc((void **)&dptr, t.size() * sizeof(int32_t)));
-    hipError_t e = hipMemcpy(dptr, t.data(), t.size() * sizeof(int32_t), hipMemcpyHostToDevice);
-    if (e != hipSuccess) {
+    WPK_HIP(hipMalloc((void **)&dptr, tap_table_bytes(pr)));
+    int rc = write_tap_table(pr, dptr, st);
+    if (rc != WPK_OK) {
         (void)hipFree(dptr);
-        set_last_hip_error((int)e);
-        return WPK_E_HIP;
+        return rc;
     }
     *out = dptr;
     return WPK_OK;
@@ -537,13 +570,13 @@ static FixupBuf g_fixup;
 static float *g_wscratch = nullptr;
 static size_t g_wscratch_elems = 0;
 
-static int get_prepared(const Problem &pr, Prepared **out)
+static int get_prepared(const Problem &pr, Prepared **out, hipStream_t st)
 {
     std::string key = desc_key(&pr.d);
     auto it = g_prepared.find(key);
     if (it == g_prepared.end()) {
         Prepared p{pr, nullptr};
-        int rc = upload_tap_table(pr, &p.ktab);
+        int rc = upload_tap_table(pr, &p.ktab, st);
         if (rc != WPK_OK) return rc;
         it = g_prepared.emplace(key, p).first;
     }
@@ -580,7 +613,7 @@ static int fwd_with(const Problem &pr, const wpk_conv_config &cfg, const float *
     int rc = ensure_device();
     if (rc != WPK_OK) return rc;
     Prepared *prep;
-    rc = get_prepared(pr, &prep);
+    rc = get_prepared(pr, &prep, st);
     if (rc != WPK_OK) return rc;
     float *wp;
     rc = get_wscratch((size_t)pr.CRSpad * pr.Kpad, &wp);
@@ -607,13 +640,20 @@ struct TuneCtx {
     FixupBuf fix;
     int rejected;
     int hip_failed;
+    int phase;                       // which stage of the search is evaluating (WPK_STAGE_*)
     std::map<int, double> times_us;  // config id -> median microseconds
+    std::map<int, int> stage_of;     // config id -> stage that first timed it
 };
 
 static int measure_us(TuneCtx &t, const wpk_conv_config &cfg, double *us_out, double *err_out)
 {
-    // one verification launch, compared on the device with the direct kernel's output
+    // one verification launch, compared on the device with the direct kernel's output; y is filled
+    // with NaN first, so an output the candidate fails to store cannot pass on the value an earlier
+    // candidate left there
     WPK_HIP(hipMemsetAsync(t.err_bits, 0, sizeof(unsigned), t.st));
+    hipLaunchKernelGGL(fill_value_kernel, dim3(1024), dim3(256), 0, t.st, t.y, (long long)t.pr.y_elems,
+                       __builtin_nanf(""));
+    WPK_HIP(hipGetLastError());
     FixupNeed need = fixup_need(t.pr, cfg, g_cus);
     if (need.bytes > 0) {
         WPK_HIP(hipStreamSynchronize(t.st));
@@ -699,6 +739,7 @@ static double tune_fitness(const int32_t *genes, int32_t n, void *user)
         return 0.0;
     }
     t->times_us[wpk_config_id(&cfg)] = us;
+    t->stage_of.emplace(wpk_config_id(&cfg), t->phase);
     if (t->opt.verbose >= 2)
         fprintf(stderr, "[wpk tune] %-32s split %2d remap %d persist %d reduce %d: %9.2f us\n",
                 wpk_config_kernel_name(&cfg), cfg.split_k, cfg.xcd_remap, cfg.persist, cfg.reduce, us);
@@ -734,7 +775,7 @@ static int tune_setup(TuneCtx &t)
     WPK_HIP(hipMalloc((void **)&t.yref, pr.y_elems * 4));
     WPK_HIP(hipMalloc((void **)&t.dref, pr.y_elems * 4));
     WPK_HIP(hipMalloc((void **)&t.err_bits, sizeof(unsigned)));
-    int rc = upload_tap_table(pr, &t.ktab);
+    int rc = upload_tap_table(pr, &t.ktab, t.st);
     if (rc != WPK_OK) return rc;
     float wscale = sqrtf(6.0f / (float)pr.CRS);  // uniform with the variance of Kaiming-normal
     hipLaunchKernelGGL(fill_hash_kernel, dim3(1024), dim3(256), 0, t.st, t.x, (long long)pr.x_elems,
@@ -778,6 +819,10 @@ struct wpk_plan {
     FixupBuf fix_side;
     std::vector<Layer> layers;
     std::vector<int32_t *> ktabs;  // one per distinct descriptor
+    // verdict of the last check whether a pass's two half-batch chains touch disjoint memory,
+    // and the pointers it was made for
+    std::vector<const float *> chk_ptrs;
+    bool chk_independent = false;
 };
 
 extern "C" {
@@ -973,6 +1018,7 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int
     t.x = t.w = t.wp = t.y = t.yref = t.dref = nullptr;
     t.err_bits = nullptr; t.ktab = nullptr;
     t.rejected = 0; t.hip_failed = 0;
+    t.phase = WPK_STAGE_SEARCH;
     rc = tune_setup(t);
     if (rc != WPK_OK) {
         tune_free(t);
@@ -1011,7 +1057,10 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int
         gens = wpk_ga_search(WPK_N_GENES, lo, hi, tune_constraint, tune_fitness, &t, &t.opt,
                              best_genes, &best_f, &evals, nullptr, nullptr, nullptr, 0);
     }
+    const double search_us = best_f > 0.0 ? 1.0 / best_f : 0.0;  // what the search alone found
+    int best_stage = WPK_STAGE_SEARCH;
     if (t.opt.mode != 2 && t.opt.refine > 0 && best_f > 0.0 && !t.hip_failed && gens >= 0) {
+        t.phase = WPK_STAGE_RULE;
         // rule-based candidates beside the search's winner: the tile shapes that exhaustive
         // searches over the workloads' layers put on top most often, each with the persistent
         // schedules and with reductions split to about 3.5 workgroups per compute unit
@@ -1059,6 +1108,7 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int
             }
         }
         // one gene of the winner at a time, every other value of it
+        t.phase = WPK_STAGE_REFINE;
         for (int round = 0; round < t.opt.refine; ++round) {
             bool moved = false;
             for (int gi = 0; gi < WPK_N_GENES; ++gi) {
@@ -1103,9 +1153,18 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int
             if (us > 0.0 && (again_best == 0 || us < again_best)) {
                 again_best = us;
                 memcpy(best_genes, g, sizeof g);
+                best_stage = t.stage_of.count(order[i].second) ? t.stage_of[order[i].second] : WPK_STAGE_SEARCH;
             }
         }
         if (again_best > 0) best_f = 1.0 / again_best;
+        // the default once more under the same protocol, so that the comparison below is between
+        // two measurements taken the same way
+        if (def_us > 0.0 && !t.hip_failed) {
+            double us = 0, err = 0;
+            int r = measure_us(t, defcfg, &us, &err);
+            if (r != WPK_OK) t.hip_failed = r;
+            else if (us > 0.0) def_us = us;
+        }
         t.opt.min_group_us = group_us;
         t.opt.reps = reps;
     }
@@ -1123,6 +1182,7 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int
         if (def_us > 0.0 && def_us < best_us) {  // never hand back something slower than the default
             best = defcfg;
             best_us = def_us;
+            best_stage = WPK_STAGE_DEFAULT;
         }
         wpk_cache_store(d, &best, best_us);
         if (report) {
@@ -1132,6 +1192,8 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int
             report->evaluations = evals;
             report->generations = gens;
             report->rejected = t.rejected;
+            report->stage = best_stage;
+            report->search_us = search_us;
             report->seconds =
                 std::chrono::duration<double>(std::chrono::steady_clock::now() - t_start).count();
         }
@@ -1176,7 +1238,7 @@ int wpk_conv_plan(const wpk_conv_desc *layers, int32_t n_layers, int32_t tune, w
         auto it = seen.find(key);
         if (it == seen.end()) {
             int32_t *ktab = nullptr;
-            rc = upload_tap_table(L.pr, &ktab);
+            rc = upload_tap_table(L.pr, &ktab, nullptr);
             if (rc != WPK_OK) break;
             plan->ktabs.push_back(ktab);
             it = seen.emplace(key, (int)plan->ktabs.size() - 1).first;
@@ -1193,6 +1255,10 @@ int wpk_conv_plan(const wpk_conv_desc *layers, int32_t n_layers, int32_t tune, w
         plan->layers.push_back(L);
         FixupNeed need = fixup_need(L.pr, L.cfg, g_cus);
         if (need.bytes > 0) rc = fixup_reserve(plan->fix, (size_t)need.bytes);
+    }
+    if (rc == WPK_OK) {  // the tap tables were written on the null stream: complete before any stream reads them
+        hipError_t e = hipDeviceSynchronize();
+        if (e != hipSuccess) { set_last_hip_error((int)e); rc = WPK_E_HIP; }
     }
     if (rc != WPK_OK) {
         wpk_plan_destroy(plan);
@@ -1326,11 +1392,61 @@ int wpk_plan_run_layer(wpk_plan *plan, int32_t layer, const float *x, float *y, 
     return wpk_plan_run_layer_fused(plan, layer, x, nullptr, y, stream);
 }
 
+// The two half-batch chains of a pipelined pass run with no ordering between them, so the pass
+// may be split only if nothing one chain writes is touched by the other chain at ANY layer.  With
+// buffers reused in turns by layers of different channel counts that fails: the second half of a
+// small tensor starts inside the first half of a large one.  The verdict is kept for the pointers
+// it was made for (a caller replays the same arrays pass after pass).
+static bool chains_independent(wpk_plan *plan, const float *const *x, const float *const *residual,
+                               float *const *y)
+{
+    const size_t nl = plan->layers.size();
+    std::vector<const float *> key(3 * nl);
+    for (size_t i = 0; i < nl; ++i) {
+        key[3 * i] = x[i];
+        key[3 * i + 1] = y[i];
+        key[3 * i + 2] = residual ? residual[i] : nullptr;
+    }
+    if (key == plan->chk_ptrs) return plan->chk_independent;
+    struct Range { uintptr_t lo, hi; };
+    auto half_of = [](const float *p, int64_t first, int64_t second, int h) {
+        Range r = {0, 0};
+        if (p) {
+            r.lo = (uintptr_t)(p + (h ? first : 0));
+            r.hi = r.lo + (uintptr_t)(h ? second : first) * sizeof(float);
+        }
+        return r;
+    };
+    auto hit = [](const Range &a, const Range &b) { return a.lo < b.hi && b.lo < a.hi; };
+    // per layer and chain: what it writes, and everything it touches
+    std::vector<Range> wr(2 * nl), rd_x(2 * nl), rd_r(2 * nl);
+    for (size_t i = 0; i < nl; ++i)
+        for (int h = 0; h < 2; ++h) {
+            const wpk_plan::Layer &L = plan->layers[i];
+            wr[2 * i + h] = half_of(y[i], L.half[0].y_elems, L.half[1].y_elems, h);
+            rd_x[2 * i + h] = half_of(x[i], L.half[0].x_elems, L.half[1].x_elems, h);
+            rd_r[2 * i + h] = half_of(residual ? residual[i] : nullptr, L.half[0].y_elems, L.half[1].y_elems, h);
+        }
+    bool ok = true;
+    for (size_t i = 0; i < nl && ok; ++i)
+        for (int h = 0; h < 2 && ok; ++h)
+            for (size_t j = 0; j < nl && ok; ++j) {
+                const int o = 1 - h;
+                ok = !hit(wr[2 * i + h], wr[2 * j + o]) && !hit(wr[2 * i + h], rd_x[2 * j + o]) &&
+                     !hit(wr[2 * i + h], rd_r[2 * j + o]);
+            }
+    plan->chk_ptrs.swap(key);
+    plan->chk_independent = ok;
+    return ok;
+}
+
 int wpk_plan_run_fused(wpk_plan *plan, const float *const *x, const float *const *residual,
                        float *const *y, void *stream)
 {
     if (!plan || !x || !y) return WPK_E_NULL_PTR;
-    if (plan->ways == 1) {
+    for (size_t i = 0; i < plan->layers.size(); ++i)
+        if (!x[i] || !y[i]) return WPK_E_NULL_PTR;
+    if (plan->ways == 1 || !chains_independent(plan, x, residual, y)) {
         const size_t nl = plan->layers.size();
         for (size_t i = 0; i < nl; ++i)
             if (!x[i] || !y[i]) return WPK_E_NULL_PTR;
@@ -1425,6 +1541,21 @@ int wpk_plan_set_layer_config(wpk_plan *plan, int32_t layer, const wpk_conv_conf
         if (rc != WPK_OK) return rc;
     }
     plan->layers[layer].cfg = *cfg;
+    // the half-batch launches of a pipelined plan follow, where the configuration is legal for them
+    if (plan->side) {
+        wpk_plan::Layer &L = plan->layers[layer];
+        for (int h = 0; h < 2; ++h) {
+            if (!legal_for(L.half[h], *cfg)) continue;
+            FixupNeed nh = fixup_need(L.half[h], *cfg, g_cus);
+            FixupBuf &fb = h == 0 ? plan->fix : plan->fix_side;
+            if (nh.bytes > (int64_t)fb.bytes) {
+                WPK_HIP(hipDeviceSynchronize());
+                int rc = fixup_reserve(fb, (size_t)nh.bytes);
+                if (rc != WPK_OK) return rc;
+            }
+            L.half_cfg[h] = *cfg;
+        }
+    }
     return WPK_OK;
 }
 

@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <map>
 #include <mutex>
 #include <numeric>
@@ -68,9 +69,19 @@ int find_variant(int bm, int bn, int bk, int wm, int wn, int stages)
 static thread_local int g_last_hip_error = 0;
 void set_last_hip_error(int e) { g_last_hip_error = e; }
 
+// Written once by the first call that looks at the device, read by every cache access.
+static std::mutex g_device_name_mu;
 static std::string g_device_name = "unknown";
-void set_device_name(const std::string &name) { g_device_name = name; }
-const std::string &device_name() { return g_device_name; }
+void set_device_name(const std::string &name)
+{
+    std::lock_guard<std::mutex> g(g_device_name_mu);
+    g_device_name = name;
+}
+std::string device_name()
+{
+    std::lock_guard<std::mutex> g(g_device_name_mu);
+    return g_device_name;
+}
 
 // Output extent along one axis by the floor rule; <= 0 if the dilated window does not fit.
 static int64_t out_extent(int64_t in, int64_t pad, int64_t dil, int64_t win, int64_t stride)
@@ -172,7 +183,7 @@ bool legal_for(const Problem &pr, const wpk_conv_config &cfg)
 // Workspace of the persistent schedule's fix-up: the tiles beyond the last whole round are shared;
 // a tile of nsteps consecutive units cut into runs of at least q units meets at most
 // ceil((nsteps-1)/q) + 1 runs (every run holds one unit when there are fewer units than runs).
-int64_t g_workspace_limit = kFixupMaxBytes;
+std::atomic<int64_t> g_workspace_limit{kFixupMaxBytes};
 
 FixupNeed fixup_need(const Problem &pr, const wpk_conv_config &cfg, int compute_units)
 {
@@ -203,7 +214,7 @@ FixupNeed fixup_need(const Problem &pr, const wpk_conv_config &cfg, int compute_
     // configurations never find slot data where counters are expected
     n.slots_offset = kFixupCounterBytes;
     n.bytes = n.slots_offset + n.shared_tiles * n.maxc * cfg.bm * cfg.bn * 4;
-    if (n.shared_tiles * 4 > kFixupCounterBytes || n.bytes > g_workspace_limit)
+    if (n.shared_tiles * 4 > kFixupCounterBytes || n.bytes > g_workspace_limit.load(std::memory_order_relaxed))
         n = FixupNeed{0, 0, 0, 0};  // use atomics
     return n;
 }
@@ -295,7 +306,7 @@ struct CacheEntry {
 };
 static std::mutex g_cache_mu;
 static std::map<std::string, CacheEntry> g_cache;
-static std::string cache_key(const wpk_conv_desc *d) { return desc_key(d) + "|" + g_device_name; }
+static std::string cache_key(const wpk_conv_desc *d) { return desc_key(d) + "|" + device_name(); }
 
 // ---- splitmix64 (Steele, Lea, Flood 2014): state += gamma; output = mix(state) -------------------
 struct SplitMix64 {
@@ -602,7 +613,7 @@ int64_t wpk_config_workspace_bytes(const wpk_conv_desc *d, const wpk_conv_config
 int wpk_set_workspace_limit(int64_t bytes)
 {
     if (bytes < 0) return WPK_E_BAD_ARG;
-    g_workspace_limit = bytes;
+    g_workspace_limit.store(bytes, std::memory_order_relaxed);
     return WPK_OK;
 }
 

@@ -4,6 +4,7 @@
 
 #include <stdint.h>
 
+#include <atomic>
 #include <string>
 #include <vector>
 
@@ -151,7 +152,7 @@ struct Epilogue {
 
 static const int64_t kFixupCounterBytes = 1 << 20;   // room for 262144 shared tiles
 static const int64_t kFixupMaxBytes = (int64_t)1 << 30;  // default cap; beyond it, atomics
-extern int64_t g_workspace_limit;  // wpk_set_workspace_limit(); set before launches are prepared
+extern std::atomic<int64_t> g_workspace_limit;  // wpk_set_workspace_limit()
 // Fix-up workspace a launch of `cfg` needs (split reduction or persistent): shared tiles, slots per tile, bytes
 // (a fixed-size counter region first, then the slots).  All zero when nothing is shared or the
 // workspace would be too large (the launch then accumulates with atomics).
@@ -163,7 +164,7 @@ FixupNeed fixup_need(const Problem &pr, const wpk_conv_config &cfg, int compute_
 // host-side state shared between wpk_host.cpp and wpk_api.hip
 void set_last_hip_error(int e);
 void set_device_name(const std::string &name);
-const std::string &device_name();
+std::string device_name();
 bool legal_for(const Problem &pr, const wpk_conv_config &cfg);
 void default_config(const Problem &pr, int compute_units, wpk_conv_config *out);
 
