@@ -23,7 +23,7 @@
  *     frees and re-allocates that scratch, which synchronises the device.  Such a call must not be
  *     recorded by a stream capture; calls after it with the same shapes only enqueue launches.
  *     They serialise on one process-wide lock while they enqueue.  Plans allocate at build time
- *     only.
+ *     only; wpk_conv2d_fwd_noalloc never allocates.
  *   - Descriptors and config structs are HOST memory, copied by value during the call.
  *   - Return value: 0 (WPK_OK) or a negative WPK_E_* code; functions that return an id return
  *     it as a non-negative int.  Nothing throws or aborts across this boundary.
@@ -54,7 +54,8 @@ enum {
     WPK_E_NO_CONFIG   = -5, /* config id out of range, or not legal for this descriptor           */
     WPK_E_BAD_ARG     = -6, /* any other invalid argument (index out of range, bad sizes ...)     */
     WPK_E_IO          = -7, /* cache file could not be read or written                            */
-    WPK_E_VERIFY      = -8  /* tuner: no candidate reproduced the reference kernel's output       */
+    WPK_E_VERIFY      = -8, /* tuner: no candidate reproduced the reference kernel's output       */
+    WPK_E_TOO_LARGE   = -9  /* wpk_conv2d_fwd_noalloc: the layer's packed weights exceed the static scratch */
 };
 
 enum { WPK_F32 = 0 };
@@ -161,6 +162,25 @@ int wpk_conv2d_fwd_fused(const wpk_conv_desc *d, const float *x, const float *w,
 int wpk_conv2d_fwd_fused_config(const wpk_conv_desc *d, const wpk_conv_config *cfg, const float *x,
                                 const float *w, const float *bias, const float *residual,
                                 int32_t relu, float *y, void *stream);
+
+/*
+ * wpk_conv2d_fwd_config for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and result
+ * (`cfg` may also be NULL: the cached tuned configuration of `d`, else the default); it calls no
+ * hipMalloc, hipFree or other allocating routine and does not synchronise.  Its lookup table,
+ * packed weights and the workspace of shared tiles live in one static device array of
+ * WPK_NOALLOC_SCRATCH_BYTES (32 MiB) that every GPU the library runs on holds until the process
+ * ends.  Limit: the packed weights, (C*R*S rounded up to 32) x (K rounded up to 128) floats, must
+ * fit 32 MiB less 1088 KiB (e.g. 3x3 with C = K = 896, or 1x1 2048 -> 3840), else WPK_E_TOO_LARGE
+ * and nothing is enqueued; where the workspace of shared tiles does not fit beside them the launch
+ * sums with atomics into y instead (zeroed by a launch of its own).  Every call on a GPU uses
+ * that GPU's one array: calls on the same stream are ordered and safe, calls that overlap on one
+ * GPU (different streams, different threads) race.  A layer outside the tiled family runs on the
+ * direct kernel, which needs no scratch.
+ */
+#define WPK_NOALLOC_SCRATCH_BYTES (32 << 20)
+int wpk_conv2d_fwd_noalloc(const wpk_conv_desc *d, const wpk_conv_config *cfg, const float *x,
+                           const float *w, float *y, void *stream);
 
 /* Plain one-output-per-lane direct kernel (no MFMA, no LDS, 64-bit indexing).  The on-device
  * reference the tuner vets candidates against; also serves shapes the tiled family rejects. */

@@ -13,8 +13,9 @@ LIB_PATH = os.path.join(_HERE, "libwpk.so")
 N_GENES = 10
 NCHW, X_NHWC, Y_NHWC, NHWC = 0, 1, 2, 3   # layout codes of ConvDesc.layout
 
-OK, E_BAD_DESC, E_NULL_PTR, E_UNSUPPORTED, E_HIP, E_NO_CONFIG, E_BAD_ARG, E_IO, E_VERIFY = (
-    0, -1, -2, -3, -4, -5, -6, -7, -8)
+(OK, E_BAD_DESC, E_NULL_PTR, E_UNSUPPORTED, E_HIP, E_NO_CONFIG, E_BAD_ARG, E_IO, E_VERIFY,
+ E_TOO_LARGE) = (0, -1, -2, -3, -4, -5, -6, -7, -8, -9)
+NOALLOC_SCRATCH_BYTES = 32 << 20
 
 DESC_FIELDS = ("n", "c", "h", "w", "k", "r", "s", "stride_h", "stride_w", "pad_h", "pad_w",
                "dil_h", "dil_w", "dtype", "layout")
@@ -111,6 +112,7 @@ def lib():
             "wpk_config_default": (I, [P(ConvDesc), P(ConvConfig)]),
             "wpk_conv2d_fwd": (I, [P(ConvDesc), V, V, V, V]),
             "wpk_conv2d_fwd_config": (I, [P(ConvDesc), P(ConvConfig), V, V, V, V]),
+            "wpk_conv2d_fwd_noalloc": (I, [P(ConvDesc), P(ConvConfig), V, V, V, V]),
             "wpk_conv2d_ref": (I, [P(ConvDesc), V, V, V, V]),
             "wpk_conv2d_fwd_fused": (I, [P(ConvDesc), V, V, V, V, ctypes.c_int32, V, V]),
             "wpk_conv2d_fwd_fused_config": (I, [P(ConvDesc), P(ConvConfig), V, V, V, V, ctypes.c_int32,
@@ -289,6 +291,12 @@ def conv2d_fwd(desc, x, w, y, stream=None):
 def conv2d_fwd_config(desc, cfg, x, w, y, stream=None):
     _check(lib().wpk_conv2d_fwd_config(ctypes.byref(desc), ctypes.byref(cfg), _ptr(x), _ptr(w),
                                        _ptr(y), _stream(stream)), "wpk_conv2d_fwd_config")
+
+
+def conv2d_fwd_noalloc(desc, x, w, y, cfg=None, stream=None):
+    _check(lib().wpk_conv2d_fwd_noalloc(ctypes.byref(desc), ctypes.byref(cfg) if cfg is not None else None,
+                                        _ptr(x), _ptr(w), _ptr(y), _stream(stream)),
+           "wpk_conv2d_fwd_noalloc")
 
 
 def conv2d_ref(desc, x, w, y, stream=None):

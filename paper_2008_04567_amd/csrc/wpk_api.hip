@@ -950,6 +950,74 @@ int wpk_conv2d_fwd(const wpk_conv_desc *d, const float *x, const float *w, float
     return fwd_with(pr, cfg, x, w, y, (hipStream_t)stream);
 }
 
+// ---- the entry point that allocates nothing ---------------------------------------------------------
+// Everything wpk_conv2d_fwd_config keeps in library-owned device memory (lookup table, packed
+// weights, arrival counters and partial-tile slots of shared tiles) lives in one static device
+// array instead.  Layout: [lookup table, 64 KiB][arrival counters, 1 MiB][slots][packed weights];
+// the counters stay where they are from call to call, so they are zero whenever a launch starts.
+// In host code the array's name is only a handle: its device address is asked for once per
+// device and kept.
+static __device__ __align__(256) unsigned char scratch[WPK_NOALLOC_SCRATCH_BYTES];
+static const int kScratchMaxDevices = 64;
+static char *g_scratch_ptr[kScratchMaxDevices];   // per device, filled on first use (under g_mu)
+static const size_t kScratchTapBytes = 64 << 10;
+static const size_t kScratchRoom = (size_t)WPK_NOALLOC_SCRATCH_BYTES - kScratchTapBytes - (size_t)kFixupCounterBytes;
+
+extern "C" int wpk_conv2d_fwd_noalloc(const wpk_conv_desc *d, const wpk_conv_config *cfg_in, const float *x,
+                                      const float *w, float *y, void *stream)
+{
+    Problem pr;
+    int rc = check_io(d, x, w, y, &pr);
+    if (rc != WPK_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (!pr.tiled_ok) {
+        if (cfg_in) return WPK_E_NO_CONFIG;
+        return run_ref(pr, x, w, y, nullptr, st);  // the direct kernel needs no scratch
+    }
+    if (cfg_in && !legal_for(pr, *cfg_in)) return WPK_E_NO_CONFIG;
+    std::lock_guard<std::mutex> g(g_mu);
+    rc = ensure_device();
+    if (rc != WPK_OK) return rc;
+    int dev = 0;
+    WPK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kScratchMaxDevices) return WPK_E_UNSUPPORTED;
+    if (!g_scratch_ptr[dev]) {
+        char *ptr = nullptr;
+        WPK_HIP(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return WPK_E_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    char *const base = g_scratch_ptr[dev];
+    wpk_conv_config cfg;
+    if (cfg_in) cfg = *cfg_in;
+    else if (wpk_cache_lookup(d, &cfg) != 1 || !legal_for(pr, cfg)) default_config(pr, g_cus, &cfg);
+    auto round256 = [](size_t v) { return (v + 255) / 256 * 256; };
+    const size_t wbytes = round256((size_t)pr.CRSpad * pr.Kpad * sizeof(float));
+    if (tap_table_bytes(pr) > kScratchTapBytes || wbytes > kScratchRoom) return WPK_E_TOO_LARGE;
+    // shared tiles meet in the slots if they fit beside the weights, else through atomics into y
+    const FixupNeed need = fixup_need(pr, cfg, g_cus);
+    const size_t slot_bytes = need.bytes > 0 ? round256((size_t)(need.bytes - need.slots_offset)) : 0;
+    FixupBuf fix;
+    fix.ptr = base + kScratchTapBytes;
+    fix.bytes = 0;
+    if (need.bytes > 0 && wbytes + slot_bytes <= kScratchRoom) fix.bytes = (size_t)need.bytes;
+    float *const wp = (float *)(base + kScratchTapBytes + kFixupCounterBytes + (fix.bytes ? slot_bytes : 0));
+    int32_t *const ktab = (int32_t *)base;
+    if (fix.bytes) {
+        // the counters this launch uses start at zero whatever an earlier call left (a fill kernel:
+        // memset nodes do not replay reliably from a captured graph)
+        const long long n4 = (need.shared_tiles + 3) / 4;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)std::min<long long>(256, (n4 + 255) / 256)), dim3(256), 0,
+                           st, (float4 *)fix.ptr, (float *)nullptr, n4, 0);
+        WPK_HIP(hipGetLastError());
+    }
+    rc = write_tap_table(pr, ktab, st);
+    if (rc != WPK_OK) return rc;
+    rc = pack_weights(pr, w, wp, st);
+    if (rc != WPK_OK) return rc;
+    return run_config(pr, cfg, ktab, x, wp, y, fix.bytes ? &fix : nullptr, st);
+}
+
 static int fwd_fused(const wpk_conv_desc *d, const wpk_conv_config *cfg_in, const float *x,
                      const float *w, const Epilogue &epi, float *y, hipStream_t st)
 {

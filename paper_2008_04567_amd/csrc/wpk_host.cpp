@@ -427,6 +427,7 @@ const char *wpk_status_string(int status)
     case WPK_E_BAD_ARG: return "bad argument";
     case WPK_E_IO: return "cache file i/o error";
     case WPK_E_VERIFY: return "no candidate passed verification";
+    case WPK_E_TOO_LARGE: return "packed weights exceed the static scratch of the entry point that does not allocate";
     }
     return status > 0 ? "ok (id)" : "unknown status";
 }
