@@ -2,10 +2,17 @@
 """Benchmark of the forward-convolution hot path on one MI355X.
 
 A step is one pass of the whole path over one batch of synthetic input: every layer of the
-workload once, through a plan (weights pre-packed at plan time, per-layer tuned configs),
+workload once, through a plan (weights pre-packed at plan time, per-layer searched configs),
 inputs and weights resident in HBM before the timed region.  Default workload: the four batched
 3x3 layers (N=16) the throughput target is quoted on.  Prints ONE JSON line on stdout; details
 go to stderr.
+
+Order of a run: search every distinct layer (genetic search on the device) -> build the plan ->
+settle phase (passes for a stated time, so that the clocks are where continuous work keeps them
+whatever --warmup says) -> W warm-up passes -> K timed passes between two synchronisations ->
+K more passes with one event per layer -> every layer's output against the CPU oracle -> the other
+workloads of the metric ("ms per conv stack") the same way, briefer -> the device's own ceilings ->
+the oracle timed on the host cores.
 """
 import argparse
 import json
@@ -18,48 +25,50 @@ sys.path.insert(0, ROOT)
 
 FP32_MFMA_PEAK_TFLOPS = 157.3   # 256 CUs x 256 FLOP/clk x 2.4 GHz
 HBM_PEAK_GBS = 8000.0           # HBM3E, published
-HBM_PEAK_GBS = 8000.0
+TOL = 1e-4                      # |y_gpu - y_oracle| <= TOL * sum|x*w| per output
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+WORKLOADS = {
+    "config3": ("config3", {}, "config3: four 3x3 s1 p1 layers, N=16, C=K in (64@56, 128@28, 256@14, 512@7)"),
+    "config4": ("config4", {}, "config4: pointwise and strided layers, N=16"),
+    "config2": ("config2", {}, "config2: 3x3 C=K=64 @56 and the 7x7/2 stem, N=1"),
+    "config1": ("config1", {}, "config1: N=1 C=K=16 14x14 3x3"),
+    "resnet50_n1": ("resnet50_stack", {"n": 1}, "config5: ResNet-50 conv stack (53 layers), N=1"),
+    "resnet50_n16": ("resnet50_stack", {"n": 16}, "config5: ResNet-50 conv stack (53 layers), N=16"),
+    "resnet18_n1": ("resnet18_stack", {"n": 1}, "ResNet-18 conv stack (20 layers), N=1"),
+    "table1": ("table1_convs", {}, "Table 1 production layers, N=1"),
+}
+
+
 def workload_layers(W, name):
-    if name == "config3":
-        return W.config3(), "config3: four 3x3 s1 p1 layers, N=16, C=K in (64@56, 128@28, 256@14, 512@7)"
-    if name == "config4":
-        return W.config4(), "config4: pointwise and strided layers, N=16"
-    if name == "config2":
-        return W.config2(), "config2: 3x3 C=K=64 @56 and the 7x7/2 stem, N=1"
-    if name == "config1":
-        return W.config1(), "config1: N=1 C=K=16 14x14 3x3"
-    if name == "resnet50_n1":
-        return W.resnet50_stack(1), "config5: ResNet-50 conv stack (53 layers), N=1"
-    if name == "resnet50_n16":
-        return W.resnet50_stack(16), "config5: ResNet-50 conv stack (53 layers), N=16"
-    if name == "resnet18_n1":
-        return W.resnet18_stack(1), "ResNet-18 conv stack (20 layers), N=1"
-    if name == "table1":
-        return W.table1_convs(), "Table 1 production layers, N=1"
-    raise SystemExit("unknown workload " + name)
+    if name not in WORKLOADS:
+        raise SystemExit("unknown workload " + name)
+    fn, kw, text = WORKLOADS[name]
+    return getattr(W, fn)(**kw), text
 
 
 def cpu_baseline(W, layers, max_seconds=25.0):
-    """The oracle as it stands, on the host cores, on a bounded sample of the workload."""
+    """The oracle as it stands, on the host cores, on a bounded sample of the workload.  Returns the
+    record and the full oracle tensors (value, normaliser) of the layers it got through."""
     import numpy as np
     from oracle import conv as oc
-    flops, secs, used, done = 0.0, 0.0, 1, []
-    for l in layers:
+    flops, secs, used, done, full = 0.0, 0.0, 1, [], {}
+    for i, l in enumerate(layers):
         x, w = W.make_inputs(l)
         sh = oc.shape_from_layer(l)
         t0 = time.perf_counter()
-        y, _, used = oc.conv2d(sh, x, w, threads=0)
+        y, d, used = oc.conv2d(sh, x, w, threads=0)
         dt = time.perf_counter() - t0
         P, Q = y.shape[2], y.shape[3]
         flops += 2.0 * l["n"] * l["k"] * P * Q * l["c"] * l["r"] * l["s"]
         secs += dt
         done.append(l["name"])
+        full[i] = (y, d)
         if secs > max_seconds:
             break
     model = ""
@@ -86,7 +95,198 @@ def cpu_baseline(W, layers, max_seconds=25.0):
     f1 = 2.0 * l["n"] * l["k"] * y.shape[2] * y.shape[3] * l["c"] * l["r"] * l["s"]
     out["single_thread"] = {"value": f1 / dt / 1e12, "unit": "TFLOP/s", "cores": 1,
                             "sample": "%s, %d images, %.1f s wall" % (l["name"], l["n"], dt)}
-    return out
+    return out, full
+
+
+def load_traffic_table(path):
+    """Rows of the tracked counter summary: layer, config id, bytes fetched and written per launch
+    (rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled as the file's header says).  {} when absent."""
+    table = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                t = line.split()
+                if len(t) >= 4 and not line.startswith("#"):
+                    table[(t[0], int(t[1]))] = (float(t[2]), float(t[3]))
+    except (OSError, ValueError):
+        pass
+    return table
+
+
+class Runner:
+    """One workload on the device: operands, plan, passes, events, oracle check."""
+
+    def __init__(self, B, W, torch, args, name, layers, descs, layout):
+        self.B, self.W, self.torch, self.args = B, W, torch, args
+        self.name, self.layers, self.descs, self.layout = name, layers, descs, layout
+        self.dev = torch.device("cuda:0")
+        self.stream = torch.cuda.current_stream()
+
+    def tune(self, opt):
+        """Search every distinct layer; returns {shape key: report fields} for the rows."""
+        B, W = self.B, self.W
+        info = {}
+        for l, d in zip(self.layers, self.descs):
+            key = W.shape_key(l)
+            if key in info:
+                continue
+            hit = B.cache_lookup(d) is not None
+            try:
+                cid, rep = B.conv_tune_ex(d, opt, force=False)
+            except B.WpkError as e:
+                if e.status != B.E_UNSUPPORTED:
+                    raise
+                log("%-28s outside the tiled family: direct kernel" % l["name"])
+                info[key] = {"found_by": "direct kernel"}
+                continue
+            if hit:
+                info[key] = {"found_by": "cache"}
+                continue
+            info[key] = {"found_by": rep.stage_name, "search_alone_us": round(rep.search_us, 2),
+                         "tuner_best_us": round(rep.best_us, 2), "tuner_default_us": round(rep.default_us, 2),
+                         "evaluations": rep.evaluations, "generations": rep.generations}
+            log("tuned %-24s %-28s split %2d remap %d persist %d reduce %d: %8.2f us by %-7s (search alone "
+                "%8.2f, default %8.2f), %d evals, %d gens, %.1f s"
+                % (l["name"], B.config_kernel_name(rep.best), rep.best.split_k, rep.best.xcd_remap,
+                   rep.best.persist, rep.best.reduce, rep.best_us, rep.stage_name, rep.search_us,
+                   rep.default_us, rep.evaluations, rep.generations, rep.seconds))
+        return info
+
+    def setup(self, epi, cold):
+        """Plan, operands on the device (distinct shapes share one x and one w), pointer arrays."""
+        B, W, torch, np = self.B, self.W, self.torch, __import__("numpy")
+        layers, descs, dev = self.layers, self.descs, self.dev
+        self.epi, self.use_res = epi, "residual" in epi
+        self.plan = B.Plan(descs, tune=False)
+        self.flops, act_bytes = [], 0
+        for l, d in zip(layers, descs):
+            P, Q = B.conv_out_shape(d)
+            self.flops.append(B.conv_flops(d))
+            act_bytes += 4 * (l["n"] * l["c"] * l["h"] * l["w"] + l["n"] * l["k"] * P * Q * (2 if self.use_res else 1))
+        # cold runs rotate through `copies` sets of activations, together above 600 MB (at most 16 GB)
+        copies = 1
+        if cold:
+            copies = max(2, min(-(-600 * 2 ** 20 // act_bytes) + 1, (16 * 2 ** 30) // act_bytes))
+        self.copies = copies
+        self.host, shared = [], {}
+        self.xs, self.ys, self.rs = ([[] for _ in range(copies)] for _ in range(3))
+        for i, (l, d) in enumerate(zip(layers, descs)):
+            key = (W.shape_key(l), l["seed"]) if copies > 1 else W.shape_key(l)
+            if key not in shared:
+                x, w = W.make_inputs(l)
+                xh = np.ascontiguousarray(x.transpose(0, 2, 3, 1)) if self.layout & 1 else x
+                shared[key] = (xh, w, [torch.from_numpy(xh).to(dev) for _ in range(copies)],
+                               torch.from_numpy(w).to(dev))
+            xh, w, xd, wd = shared[key]
+            self.host.append((xh, w))
+            P, Q = B.conv_out_shape(d)
+            yshape = (l["n"], P, Q, l["k"]) if self.layout & 2 else (l["n"], l["k"], P, Q)
+            for c in range(copies):
+                self.xs[c].append(xd[c])
+                self.ys[c].append(torch.empty(yshape, device=dev, dtype=torch.float32))
+                self.rs[c].append(torch.rand(yshape, device=dev, dtype=torch.float32) if self.use_res else None)
+            self.plan.set_weights(i, wd)
+            if epi:
+                self.plan.set_epilogue(i, torch.zeros(l["k"], device=dev, dtype=torch.float32)
+                                       if "bias" in epi else None, relu="relu" in epi)
+        self.arrays = [self.plan.pointer_arrays(self.xs[c], self.ys[c]) + (self.plan.residual_array(self.rs[c]),)
+                       for c in range(copies)]
+        torch.cuda.synchronize()
+
+    def one_pass(self, step):
+        xa, ya, ra = self.arrays[step % self.copies]
+        if self.use_res:
+            self.plan.run_fused(xa, ra, ya, self.stream)
+        else:
+            self.plan.run(xa, ya, self.stream)
+
+    def settle(self, settle_ms):
+        """Passes back to back until at least settle_ms of GPU work have gone by, in batches sized
+        from a first measured pass so the queue never runs dry; returns (passes, ms)."""
+        torch = self.torch
+        if settle_ms <= 0:
+            return 0, 0.0
+        t0 = time.perf_counter()
+        self.one_pass(0)
+        torch.cuda.synchronize()
+        est = max(time.perf_counter() - t0, 2e-5)
+        done, t0 = 1, time.perf_counter()
+        while (time.perf_counter() - t0) * 1e3 < settle_ms:
+            batch = max(1, min(2000, int(0.01 / est)))       # about 10 ms of work per batch
+            for s_ in range(batch):
+                self.one_pass(done + s_)
+            done += batch
+            torch.cuda.synchronize()
+        return done, (time.perf_counter() - t0) * 1e3
+
+    def timed(self, steps, warmup):
+        """W warm-up passes, then exactly `steps` passes between two synchronisations."""
+        torch = self.torch
+        for s_ in range(warmup):
+            self.one_pass(s_)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s_ in range(steps):
+            self.one_pass(s_)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    def per_layer_events(self, steps):
+        """`steps` passes layer by layer with an event after every layer on the launch stream."""
+        torch, np, n = self.torch, __import__("numpy"), len(self.layers)
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(n + 1)] for _ in range(steps)]
+        for s in range(steps):
+            ev[s][0].record(self.stream)
+            c = s % self.copies
+            for i in range(n):
+                self.plan.run_layer_fused(i, self.xs[c][i], self.rs[c][i], self.ys[c][i], self.stream)
+                ev[s][i + 1].record(self.stream)
+        torch.cuda.synchronize()
+        return [[1e3 * ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(steps)] for i in range(n)]
+
+    def check(self, full, samples):
+        """Max normalised error of every layer's output (as the last pass left it) against the oracle:
+        the whole tensor where `full` holds the oracle's (plain runs) or the run is fused or
+        channels-last on a small enough layer, else `samples` outputs computed one by one."""
+        np = __import__("numpy")
+        from oracle import conv as oc
+        errs, kinds = [], []
+        xl, yl = ("NHWC" if self.layout & 1 else "NCHW"), ("NHWC" if self.layout & 2 else "NCHW")
+        plain = not self.epi and self.layout == 0
+        for i, l in enumerate(self.layers):
+            c = (self.args.steps - 1) % self.copies if self.copies > 1 else 0
+            y_gpu = self.ys[c][i].cpu().numpy().astype(np.float64)
+            sh = oc.shape_from_layer(l)
+            xh, w = self.host[i]
+            if plain and i in full:
+                y_ref, d_ref = full[i]
+                kinds.append("full")
+            elif not plain and self.flops[i] <= 8e9:
+                bias = np.zeros(l["k"], np.float32) if "bias" in self.epi else None
+                res = self.rs[c][i].cpu().numpy() if self.use_res else None
+                y_ref, d_ref = oc.conv2d_fused(sh, xh, w, bias=bias, residual=res, relu="relu" in self.epi,
+                                               x_layout=xl, y_layout=yl)
+                kinds.append("full")
+            elif plain:
+                total = y_gpu.size
+                pq = y_gpu.shape[2] * y_gpu.shape[3]
+                idx = np.random.default_rng(i).integers(0, total, size=min(samples, total))
+                idx = np.unique(np.concatenate([idx, [0, total - 1, pq - 1, total - pq]]))
+                y_ref, d_ref = oc.conv2d_sampled(sh, xh, w, idx)
+                y_gpu = y_gpu.reshape(-1)[idx]
+                kinds.append("%d sampled" % idx.size)
+            else:
+                errs.append(None)
+                kinds.append("not checked (fused or channels-last layer too large for a full oracle pass)")
+                continue
+            y_gpu = y_gpu.reshape(y_ref.shape)
+            zero = d_ref == 0
+            if not np.all(np.isfinite(y_gpu)) or not np.all(y_gpu[zero] == 0.0):
+                errs.append(float("inf"))
+                continue
+            e = np.abs(y_gpu - y_ref) / np.where(zero, 1.0, d_ref)
+            errs.append(float(e.max()) if e.size else 0.0)
+        return errs, kinds
 
 
 def main():
@@ -95,10 +295,15 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="config3")
+    ap.add_argument("--settle-ms", type=float, default=150.0,
+                    help="continuous passes for at least this long before the warm-up passes (0: none)")
+    ap.add_argument("--stacks", default="config4,resnet50_n16,resnet50_n1",
+                    help="other workloads searched, timed and checked after the headline one, reported under "
+                         "'stacks' (ms per pass); empty string: none")
     ap.add_argument("--no-tune", action="store_true", help="use the untuned default configs")
     ap.add_argument("--cache", default=None, help="search-result cache file to load/save")
     ap.add_argument("--tune-mode", type=int, default=0, help="0 genetic, 1 random, 2 exhaustive")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline (and the full-tensor check)")
     ap.add_argument("--verbose-tune", action="store_true")
     ap.add_argument("--cold", action="store_true",
                     help="rotate x and y through a pool larger than the 256 MB memory-side cache, so "
@@ -131,131 +336,68 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     dev_name, cus = B.device_info()
-    layers, wl_text = workload_layers(W, args.workload)
     layout = {"nchw": B.NCHW, "nhwc": B.NHWC, "x_nhwc": B.X_NHWC, "y_nhwc": B.Y_NHWC}[args.layout]
-    descs = [B.make_desc(l, layout=layout) for l in layers]
-    log("device %s, %d CUs; workload %s" % (dev_name, cus, wl_text))
+    epi = set(t for t in args.fused.split(",") if t)
+    assert epi <= {"bias", "residual", "relu"}, "--fused takes bias,residual,relu"
 
     if args.workspace_limit is not None:
         B.set_workspace_limit(args.workspace_limit)
     if args.cache and os.path.exists(args.cache):
         log("loaded %d cached search results" % B.cache_load(args.cache))
-    t_tune = time.perf_counter()
-    if not args.no_tune:
-        # the timed region runs whole passes of a plan on separate buffers: outputs that a layer sums
-        # into with atomics are zeroed once per pass, so candidates are timed without that launch
-        opt = B.tune_default_options(mode=args.tune_mode, verbose=1 if args.verbose_tune else 0,
-                                     zero_ahead=0 if args.pipeline == 2 else 1,
-                                     epilogue=1 if args.fused else 0)
-        if args.refine is not None:
-            opt.refine = args.refine
-        seen = set()
-        for l, d in zip(layers, descs):
-            key = W.shape_key(l)
-            if key in seen:
-                continue
-            seen.add(key)
-            hit = B.cache_lookup(d) is not None
-            try:
-                cid, rep = B.conv_tune_ex(d, opt, force=False)
-            except B.WpkError as e:
-                if e.status != B.E_UNSUPPORTED:
-                    raise
-                log("%-28s outside the tiled family: direct kernel" % l["name"])
-                continue
-            if not hit:
-                log("tuned %-28s %-30s split %2d remap %d persist %d reduce %d: %8.2f us (default %8.2f us), "
-                    "%d evals, %d gens, %.1f s" % (l["name"], B.config_kernel_name(rep.best),
-                                         rep.best.split_k, rep.best.xcd_remap, rep.best.persist,
-                                         rep.best.reduce,
-                                         rep.best_us, rep.default_us,
-                                         rep.evaluations, rep.generations, rep.seconds))
+    # the timed region runs whole passes of a plan on separate buffers: outputs that a layer sums
+    # into with atomics are zeroed once per pass, so candidates are timed without that launch
+    opt = B.tune_default_options(mode=args.tune_mode, verbose=1 if args.verbose_tune else 0,
+                                 zero_ahead=0 if args.pipeline == 2 else 1, epilogue=1 if epi else 0)
+    if args.refine is not None:
+        opt.refine = args.refine
+
+    def prepare(name):
+        layers, text = workload_layers(W, name)
+        descs = [B.make_desc(l, layout=layout) for l in layers]
+        r = Runner(B, W, torch, args, name, layers, descs, layout)
+        t0 = time.perf_counter()
+        info = {} if args.no_tune else r.tune(opt)
+        if args.pipeline == 2 and not args.no_tune:     # the half-batch shapes get their own search
+            for l in layers:
+                for nh in {(l["n"] + 1) // 2, l["n"] // 2}:
+                    dh = B.make_desc(dict(l, n=nh), layout=layout)
+                    if B.cache_lookup(dh) is None:
+                        try:
+                            B.conv_tune_ex(dh, opt, force=False)
+                        except B.WpkError as e:
+                            if e.status != B.E_UNSUPPORTED:
+                                raise
         if args.cache:
             B.cache_save(args.cache)
-    if args.pipeline == 2 and not args.no_tune:     # the half-batch shapes get their own search
-        for l in layers:
-            for nh in {(l["n"] + 1) // 2, l["n"] // 2}:
-                dh = B.make_desc(dict(l, n=nh), layout=layout)
-                if B.cache_lookup(dh) is None:
-                    try:
-                        B.conv_tune_ex(dh, opt, force=False)
-                    except B.WpkError as e:
-                        if e.status != B.E_UNSUPPORTED:
-                            raise
-        if args.cache:
-            B.cache_save(args.cache)
-    t_tune = time.perf_counter() - t_tune
+        return r, text, info, time.perf_counter() - t0
 
-    epi = set(t for t in args.fused.split(",") if t)
-    assert epi <= {"bias", "residual", "relu"}, "--fused takes bias,residual,relu"
-    use_res = "residual" in epi
-    plan = B.Plan(descs, tune=False)
-    flops, act_bytes = [], 0
-    for l, d in zip(layers, descs):
-        P, Q = B.conv_out_shape(d)
-        flops.append(B.conv_flops(d))
-        act_bytes += 4 * (l["n"] * l["c"] * l["h"] * l["w"] + l["n"] * l["k"] * P * Q * (2 if use_res else 1))
-    # cold runs rotate through `copies` sets of activations, together above 600 MB (at most 16 GB)
-    copies = 1
-    if args.cold:
-        copies = max(2, min(-(-600 * 2 ** 20 // act_bytes) + 1, (16 * 2 ** 30) // act_bytes))
-    xs, ys, rs = [[] for _ in range(copies)], [[] for _ in range(copies)], [[] for _ in range(copies)]
-    for i, (l, d) in enumerate(zip(layers, descs)):
-        x, w = W.make_inputs(l)
-        P, Q = B.conv_out_shape(d)
-        xh = torch.from_numpy(np.ascontiguousarray(x.transpose(0, 2, 3, 1)) if layout & 1 else x)
-        for c in range(copies):
-            xs[c].append(xh.to(dev))
-            ys[c].append(torch.empty((l["n"], l["k"], P, Q), device=dev, dtype=torch.float32))
-            rs[c].append(torch.rand((l["n"], l["k"], P, Q), device=dev, dtype=torch.float32)
-                         if use_res else None)
-        plan.set_weights(i, torch.from_numpy(w).to(dev))
-        if epi:
-            plan.set_epilogue(i, torch.zeros(l["k"], device=dev, dtype=torch.float32)
-                              if "bias" in epi else None, relu="relu" in epi)
-    arrays = [plan.pointer_arrays(xs[c], ys[c]) + (plan.residual_array(rs[c]),) for c in range(copies)]
-    stream = torch.cuda.current_stream()
-    torch.cuda.synchronize()
-
-    def one_pass(step):
-        xa, ya, ra = arrays[step % copies]
-        if use_res:
-            plan.run_fused(xa, ra, ya, stream)
-        else:
-            plan.run(xa, ya, stream)
-
+    # ---- the headline workload ------------------------------------------------------------------
+    run, wl_text, tune_info, t_tune = prepare(args.workload)
+    layers, descs = run.layers, run.descs
+    log("device %s, %d CUs; workload %s" % (dev_name, cus, wl_text))
+    run.setup(epi, args.cold)
     if args.pipeline == 2:
-        plan.set_pipeline(2)
-    for s_ in range(args.warmup):
-        one_pass(s_)
-    torch.cuda.synchronize()
-
-    # ---- timed region: exactly `steps` passes, bracketed by synchronisation -----------------
-    t0 = time.perf_counter()
-    for s_ in range(args.steps):
-        one_pass(s_)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
+        run.plan.set_pipeline(2)
+    settle_passes, settle_ms = run.settle(args.settle_ms)
+    # timed region: exactly `steps` passes, bracketed by synchronisation
+    ms_per_step = run.timed(args.steps, args.warmup)
+    flops = run.flops
     total_flops = float(sum(flops))
     value = total_flops / (ms_per_step * 1e-3) / 1e12
-
-    plan.set_pipeline(1)
-    # ---- per-layer durations with events on the launch stream (same steps count) -------------
-    n = len(layers)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(n + 1)] for _ in range(args.steps)]
-    for s in range(args.steps):
-        ev[s][0].record(stream)
-        c = s % copies
-        for i in range(n):
-            plan.run_layer_fused(i, xs[c][i], rs[c][i], ys[c][i], stream)
-            ev[s][i + 1].record(stream)
-    torch.cuda.synchronize()
-    samples_us = [[1e3 * ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(args.steps)] for i in range(n)]
+    run.plan.set_pipeline(1)
+    samples_us = run.per_layer_events(args.steps)
     per_layer_us = [float(np.mean(v)) for v in samples_us]
+
+    # ---- the oracle: timed on the host cores, and every layer's device output held to it ---------
+    cpu_rec, full = (None, {}) if args.no_cpu else cpu_baseline(W, layers)
+    errs, err_kinds = run.check(full, 4096)
+    traffic = load_traffic_table(TRAFFIC_TABLE)
+
+    n = len(layers)
     rows = []
+    use_res = "residual" in epi
     for i, l in enumerate(layers):
-        cfg = plan.layer_config(i)
+        cfg = run.plan.layer_config(i)
         tf = flops[i] / (per_layer_us[i] * 1e-6) / 1e12
         d = descs[i]
         P, Q = B.conv_out_shape(d)
@@ -264,29 +406,44 @@ def main():
         gbs = abytes / (per_layer_us[i] * 1e-6) / 1e9
         # which roofline bounds the layer: the longer of flops at MFMA peak and bytes at HBM peak
         bound = "mfma" if flops[i] / (FP32_MFMA_PEAK_TFLOPS * 1e12) >= abytes / (HBM_PEAK_GBS * 1e9) else "hbm"
-        rows.append({"layer": l["name"], "kernel": B.config_kernel_name(cfg), "split_k": cfg.split_k,
-                     "xcd_remap": cfg.xcd_remap, "persist": cfg.persist, "stages": cfg.stages,
-                     "reduce": "atomics" if cfg.reduce else "workspace",
-                     "us": round(per_layer_us[i], 2), "us_median": round(float(np.median(samples_us[i])), 2),
-                     "us_min": round(float(np.min(samples_us[i])), 2),
-                     "tflops": round(tf, 2), "pct_fp32_mfma_peak": round(100 * tf / FP32_MFMA_PEAK_TFLOPS, 1),
-                     "gbs_algorithmic": round(gbs, 1), "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1),
-                     "bound": bound, "flops": flops[i], "bytes_algorithmic": abytes})
-        log("%-28s %-30s split %2d persist %d  %9.2f us  %7.2f TFLOP/s  %5.1f%% of fp32 MFMA peak  "
-            "%7.1f GB/s  %4.1f%% of HBM peak  (%s-bound)"
-            % (l["name"], rows[-1]["kernel"], cfg.split_k, cfg.persist, per_layer_us[i], tf,
-               rows[-1]["pct_fp32_mfma_peak"], gbs, rows[-1]["pct_hbm_peak"], bound))
+        row = {"layer": l["name"], "kernel": B.config_kernel_name(cfg), "config_id": B.config_id(cfg),
+               "split_k": cfg.split_k, "xcd_remap": cfg.xcd_remap, "persist": cfg.persist, "stages": cfg.stages,
+               "reduce": "atomics" if cfg.reduce else "workspace",
+               "us": round(per_layer_us[i], 2), "us_median": round(float(np.median(samples_us[i])), 2),
+               "us_min": round(float(np.min(samples_us[i])), 2),
+               "tflops": round(tf, 2), "pct_fp32_mfma_peak": round(100 * tf / FP32_MFMA_PEAK_TFLOPS, 1),
+               "gbs_algorithmic": round(gbs, 1), "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1),
+               "bound": bound, "flops": flops[i], "bytes_algorithmic": abytes,
+               "max_norm_err": errs[i], "checked": err_kinds[i]}
+        row.update(tune_info.get(W.shape_key(l), {"found_by": "default (no search)"}))
+        hit = traffic.get((l["name"], row["config_id"])) if layout == 0 and not epi else None
+        if hit:
+            row["traffic_bytes"] = {"fetched": hit[0], "written": hit[1],
+                                    "over_algorithmic": round((hit[0] + hit[1]) / abytes, 2)}
+        rows.append(row)
+        log("%-24s %-28s split %2d persist %d %8.2f us %7.2f TFLOP/s %5.1f%% of fp32 MFMA peak %7.1f GB/s "
+            "%4.1f%% of HBM peak (%s-bound) err %s (%s) by %s"
+            % (l["name"], row["kernel"], cfg.split_k, cfg.persist, per_layer_us[i], tf,
+               row["pct_fp32_mfma_peak"], gbs, row["pct_hbm_peak"], bound,
+               "%.2g" % errs[i] if errs[i] is not None else "-", err_kinds[i], row["found_by"]))
     dom = int(np.argmax(per_layer_us))
+    tb = rows[dom].get("traffic_bytes")
+    traffic_dom = tb["fetched"] + tb["written"] if tb else None
     if rows[dom]["bound"] == "mfma":
         roofline = {"bound": "mfma", "achieved": rows[dom]["tflops"], "peak": FP32_MFMA_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(rows[dom]["tflops"] / FP32_MFMA_PEAK_TFLOPS, 4),
-                    "traffic": None, "flops_per_launch": flops[dom]}
+                    "traffic": traffic_dom, "flops_per_launch": flops[dom]}
     else:
         roofline = {"bound": "hbm", "achieved": rows[dom]["gbs_algorithmic"], "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(rows[dom]["gbs_algorithmic"] / HBM_PEAK_GBS, 4),
-                    "traffic": None, "bytes_per_launch": rows[dom]["bytes_algorithmic"]}
+                    "traffic": traffic_dom, "bytes_per_launch": rows[dom]["bytes_algorithmic"]}
     roofline.update({"kernel": rows[dom]["kernel"], "layer": rows[dom]["layer"],
-                     "avg_us": round(per_layer_us[dom], 2)})
+                     "avg_us": round(per_layer_us[dom], 2),
+                     "traffic_unit": "bytes per launch, fetched + written, from profiles/%s"
+                                     % os.path.basename(TRAFFIC_TABLE) if traffic_dom else
+                                     "null: no counter run on record for this layer under this configuration"})
+    checked = [e for e in errs if e is not None]
+    worst = max(checked) if checked else None
 
     out = {"metric": "conv2d fwd TFLOP/s (fp32, direct-convolution FLOP count) over the layer set",
            "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -294,18 +451,61 @@ def main():
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": wl_text, "layers": n, "tuned": not args.no_tune,
                       "tune_seconds": round(t_tune, 1),
-                      "activations": "rotated through %d copies (read from HBM)" % copies if args.cold
+                      "settle_ms": round(settle_ms, 1), "settle_passes": settle_passes,
+                      "activations": "rotated through %d copies (read from HBM)" % run.copies if args.cold
                                      else "one set, resident in the memory-side cache between passes",
                       "epilogue": "fused: " + "+".join(sorted(epi)) if epi else "none",
                       "layout": args.layout,
                       "schedule": "two half-batch chains on two streams" if args.pipeline == 2
                                   else "one launch per layer on one stream"},
            "pct_fp32_mfma_peak": round(100 * value / FP32_MFMA_PEAK_TFLOPS, 2),
+           "max_norm_err": worst, "tolerance": TOL,
            "roofline": roofline, "layers": rows}
+    run.plan.destroy()
+    del run
+
+    # ---- the rest of the metric: ms per pass of the other workloads -----------------------------
+    stacks = {}
+    for name in [s for s in args.stacks.split(",") if s and s != args.workload]:
+        t0 = time.perf_counter()
+        r, text, info, t_search = prepare(name)
+        r.setup(epi, False)
+        r.settle(min(args.settle_ms, 60.0))
+        k = max(args.steps, 20)
+        ms = r.timed(k, max(args.warmup, 3))
+        per = [float(np.mean(v)) for v in r.per_layer_events(min(k, 20))]
+        e, kinds = r.check({}, 2048)
+        ce = [v for v in e if v is not None]
+        tfl = float(sum(r.flops)) / (ms * 1e-3) / 1e12
+        slow = int(np.argmax([p / max(f, 1.0) for p, f in zip(per, r.flops)]))
+        found = {}
+        for v in info.values():
+            found[v["found_by"]] = found.get(v["found_by"], 0) + 1
+        stacks[name] = {"workload": text, "layers": len(r.layers), "distinct_layers": len(info) or None,
+                        "ms_per_pass": round(ms, 5), "steps": k, "tflops": round(tfl, 2),
+                        "pct_fp32_mfma_peak": round(100 * tfl / FP32_MFMA_PEAK_TFLOPS, 2),
+                        "sum_layer_us": round(float(sum(per)), 1),
+                        "max_norm_err": max(ce) if ce else None, "layers_checked": len(ce),
+                        "check": "2048 sampled outputs per layer against the oracle",
+                        "winners_found_by": found, "search_seconds": round(t_search, 1),
+                        "slowest_per_flop": {"layer": r.layers[slow]["name"], "us": round(per[slow], 2),
+                                             "tflops": round(r.flops[slow] / per[slow] / 1e6, 2)},
+                        "layer_us": {l["name"]: round(p, 2) for l, p in zip(r.layers, per)}}
+        log("stack %-14s %3d layers  %.4f ms per pass  %6.2f TFLOP/s  max err %s  (%.1f s)"
+            % (name, len(r.layers), ms, tfl, "%.2g" % max(ce) if ce else "-", time.perf_counter() - t0))
+        r.plan.destroy()
+        del r
+        torch.cuda.empty_cache()
+    if stacks:
+        out["stacks"] = stacks
+        errs_all = [v["max_norm_err"] for v in stacks.values() if v["max_norm_err"] is not None]
+        if worst is not None and errs_all:
+            out["max_norm_err_all_workloads"] = max([worst] + errs_all)
+
     if not args.no_peaks:
         # the device's own ceilings, after the timed region: sustained clocks under matrix load lie
         # below the 2.4 GHz the published peak assumes
-        burst, sustained, copy_gbs = B.measure_peaks(60.0, stream)
+        burst, sustained, copy_gbs = B.measure_peaks(60.0, torch.cuda.current_stream())
         out["measured_peaks"] = {"fp32_mfma_tflops_after_pause": round(burst, 1),
                                  "fp32_mfma_tflops_sustained": round(sustained, 1),
                                  "copy_gbs_read_plus_written": round(copy_gbs, 1),
@@ -322,10 +522,13 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         log("calibration: 3 device copies of 256 MiB read + 256 MiB written")
-    if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(W, layers)
-    plan.destroy()
+    if cpu_rec is not None:
+        out["cpu_baseline"] = cpu_rec
     print(json.dumps(out), flush=True)
+    bad = [v for v in [worst] + [s["max_norm_err"] for s in stacks.values()] if v is not None and not v <= TOL]
+    if bad:
+        log("FAILED: an output differs from the oracle by more than %g of its normaliser" % TOL)
+        sys.exit(1)
 
 
 if __name__ == "__main__":
