@@ -95,7 +95,7 @@ int wpk_last_hip_error(void);
  * wpk_config_legal() says so (the constraint check of Step1): the tile combination must be one
  * the library was built with, its LDS and workgroup size must fit a gfx950 compute unit,
  * split_k may not exceed the number of reduction steps, and the persistent schedule excludes
- * split_k > 1 and xcd_remap.
+ * split_k > 1.
  */
 #define WPK_N_GENES 10
 typedef struct wpk_conv_config {
@@ -105,10 +105,12 @@ typedef struct wpk_conv_config {
     int32_t wm;        /* waves along the pixel dimension:       1, 2, 4                            */
     int32_t wn;        /* waves along the channel dimension:     1, 2, 4                            */
     int32_t split_k;   /* slices of the reduction done by separate workgroups: 1 .. 16, 20, 24     */
-    int32_t xcd_remap; /* 0: tiles in launch order; 1: contiguous tile ranges per XCD              */
+    int32_t xcd_remap; /* 0: tiles in launch order; 1: contiguous tile ranges per XCD (persistent:   */
+                       /* within each whole round of tiles)                                        */
     int32_t persist;   /* 0: one workgroup per tile and slice; 1..4: that many persistent          */
                        /* workgroups per compute unit, the reduction steps of the tiles that do   */
-                       /* not fill a whole round dealt out evenly among them (split_k must be 1)   */
+                       /* not fill a whole round dealt out evenly among them and done first       */
+                       /* (split_k must be 1)                                                      */
     int32_t stages;    /* input tiles in flight in registers between global memory and LDS: 1..3   */
     int32_t reduce;    /* how workgroups that share a tile (split_k > 1 or persist > 0) add up:      */
                        /* 0: partial tiles through a device workspace, the last to arrive sums and */

@@ -9,7 +9,8 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libwpk.so")
+# WPK_LIBRARY names another build of the library (same ABI) to load instead of the in-tree one
+LIB_PATH = os.environ.get("WPK_LIBRARY") or os.path.join(_HERE, "libwpk.so")
 N_GENES = 10
 NCHW, X_NHWC, Y_NHWC, NHWC = 0, 1, 2, 3   # layout codes of ConvDesc.layout
 

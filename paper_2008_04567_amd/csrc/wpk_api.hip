@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -30,11 +31,11 @@ namespace wpk {
 typedef hipError_t (*LaunchFn)(const IgemmArgs &, hipStream_t);
 #define WPK_VARIANT(PART, BM, BN, BK, WM, WN, PD) \
     extern template hipError_t launch_igemm<BM, BN, BK, WM, WN, PD>(const IgemmArgs &, hipStream_t);
-#include "wpk_variants.def"
+#include WPK_VARIANTS_FILE
 #undef WPK_VARIANT
 #define WPK_VARIANT(PART, BM, BN, BK, WM, WN, PD) &launch_igemm<BM, BN, BK, WM, WN, PD>,
 static const LaunchFn kLaunch[] = {
-#include "wpk_variants.def"
+#include WPK_VARIANTS_FILE
 };
 #undef WPK_VARIANT
 
@@ -286,8 +287,9 @@ static int ensure_device()
 //  - Three tail tables [32 rows], for K-steps of 8, 16 and 32: the rows from the start of the last
 //    step of the reduction, with absolute offsets; rows past C*R*S point at the always-set bit 31.
 // Layout: periodic | tail(8) | tail(16) | tail(32).
-// Channels-last in channel quads (quad != 0): one entry per filter tap instead, {byte offset of the
-// tap (biased like the descriptor base), mask bits}, padded with zero entries to 32.
+// Tap-major forms (quad != 0: channels-last in channel quads, or [N][C][H][W] with C a multiple of
+// every K-step): one entry per filter tap instead, {byte offset of the tap (biased like the
+// descriptor base), mask bits}, padded with zero entries to 32.
 // The tables are written on the device (one lane per entry) so that preparing a descriptor is a
 // launch on the caller's stream and nothing else: no host-to-device copy, no synchronisation.
 struct TapGeom {
@@ -305,9 +307,9 @@ static TapGeom tap_geometry(const Problem &pr)
     g.pad_h = d.pad_h; g.pad_w = d.pad_w; g.dil_h = d.dil_h; g.dil_w = d.dil_w;
     g.cs = pr.xl ? 1 : d.h * d.w;
     g.ps = pr.xl ? d.c : 1;
-    g.quad = pr.xquad ? 1 : 0;
+    g.quad = pr.xquad || pr.tapmajor ? 1 : 0;
     const int RS = d.r * d.s;
-    g.entries = pr.xquad ? std::max(RS, 32) : (RS + 3) * 32;
+    g.entries = g.quad ? std::max(RS, 32) : (RS + 3) * 32;
     return g;
 }
 static size_t tap_table_bytes(const Problem &pr) { return (size_t)tap_geometry(pr).entries * 2 * sizeof(int32_t); }
@@ -321,8 +323,8 @@ __global__ void __launch_bounds__(256) tap_table_kernel(int32_t *__restrict__ t,
     if (g.quad) {
         if (e < RS) {
             const int r = e / g.S, s = e - r * g.S;
-            // ((r*dil_h - pad_h)*W + s*dil_w - pad_w)*C*4 plus the bias (pad_h*W + pad_w)*C*4
-            off = (r * g.dil_h * g.W + s * g.dil_w) * g.C * 4;
+            // ((r*dil_h - pad_h)*W + s*dil_w - pad_w)*ps*4 plus the bias (pad_h*W + pad_w)*ps*4
+            off = (r * g.dil_h * g.W + s * g.dil_w) * g.ps * 4;
             bits = r | (16 + s) << 8;
         }
     } else {
@@ -375,7 +377,7 @@ static int pack_weights(const Problem &pr, const float *w, float *wp, hipStream_
 {
     dim3 grid(pr.CRSpad / 32, pr.Kpad / 32);
     hipLaunchKernelGGL(pack_weights_kernel, grid, dim3(256), 0, st, w, wp, pr.d.k, pr.CRS, pr.Kpad, pr.d.c,
-                       pr.xquad ? pr.d.r * pr.d.s : 0);
+                       pr.xquad || pr.tapmajor ? pr.d.r * pr.d.s : 0);
     WPK_HIP(hipGetLastError());
     return WPK_OK;
 }
@@ -493,7 +495,7 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     a.remap = cfg.xcd_remap;
     a.x_bytes = (uint32_t)(pr.x_elems * 4);
     a.x_bias = (uint32_t)((d.pad_h * d.w + d.pad_w) * 4 * (pr.xl ? d.c : 1));
-    a.xl = pr.xquad ? 2 : pr.xl ? 1 : 0;
+    a.xl = pr.xquad ? 2 : pr.tapmajor ? 3 : pr.xl ? 1 : 0;
     a.yl = pr.yl ? 1 : 0;
     // whole channel quads with 16-byte stores when the tensors allow it
     if (pr.yl && d.k % 4 == 0 && ((uintptr_t)y & 15) == 0 && ((uintptr_t)epi.res & 15) == 0 &&
@@ -1152,8 +1154,12 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int
                 wpk_conv_config c = {sh[0], sh[1], sh[2], sh[3], sh[4], 1, 0, 0, sh[5], 0};
                 for (int p = 2; p <= 4; ++p) {
                     c.persist = p;
-                    c.reduce = 0;
-                    consider(c);
+                    for (int remap = 0; remap < 2; ++remap) {
+                        c.xcd_remap = remap;
+                        c.reduce = 0;
+                        consider(c);
+                    }
+                    c.xcd_remap = 0;
                     c.reduce = 1;
                     consider(c);
                 }

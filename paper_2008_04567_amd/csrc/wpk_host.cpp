@@ -51,7 +51,7 @@ const int32_t *gene_values(int g)
     {BM, BN, BK, WM, WN, PD,                                                                       \
      "wpk_igemm_" WPK_STR(BM) "x" WPK_STR(BN) "x" WPK_STR(BK) "_" WPK_STR(WM) "x" WPK_STR(WN) "_p" WPK_STR(PD)},
 const Variant kVariants[] = {
-#include "wpk_variants.def"
+#include WPK_VARIANTS_FILE
 };
 #undef WPK_VARIANT
 const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
@@ -118,6 +118,7 @@ int make_problem(const wpk_conv_desc *d, Problem *out)
     pr.Kpad = (d->k + kKoutAlign - 1) / kKoutAlign * kKoutAlign;
     pr.xl = (d->layout & 1) != 0;
     pr.xquad = pr.xl && d->c % kRedAlign == 0;
+    pr.tapmajor = !pr.xl && d->c % kRedAlign == 0;
     pr.yl = (d->layout & 2) != 0;
     int64_t bias = ((int64_t)d->pad_h * d->w + d->pad_w) * 4 * (pr.xl ? d->c : 1);
     pr.tiled_ok = d->r <= kMaxFilterRows && d->s <= kMaxFilterCols &&
@@ -169,8 +170,8 @@ bool legal_for(const Problem &pr, const wpk_conv_config &cfg)
     if (threads > cfg.bm && (cfg.bk * cfg.bm / threads) % 4 != 0) return false;   // whole k quads per thread
     int32_t nsteps = (pr.CRS + cfg.bk - 1) / cfg.bk;
     if (cfg.split_k > nsteps) return false;
-    // the persistent schedule balances the reduction itself: no fixed slices, no tile remap
-    if (cfg.persist > 0 && (cfg.split_k != 1 || cfg.xcd_remap != 0)) return false;
+    // the persistent schedule balances the reduction itself: no fixed slices
+    if (cfg.persist > 0 && cfg.split_k != 1) return false;
     // how partial tiles meet is a choice only where tiles can be shared
     if (cfg.reduce != 0 && cfg.split_k == 1 && cfg.persist == 0) return false;
     int64_t tiles = ((pr.M + cfg.bm - 1) / cfg.bm) * ((pr.d.k + cfg.bn - 1) / cfg.bn);
@@ -245,7 +246,7 @@ void default_config(const Problem &pr, int compute_units, wpk_conv_config *out)
         wpk_conv_config h = c;
         h.bk = pr.CRS >= 32 ? 16 : 8;
         h.split_k = 1;
-        h.xcd_remap = 0;
+        h.xcd_remap = 1;
         h.persist = 3;
         h.reduce = 0;
         if (legal_for(pr, h)) {

@@ -94,6 +94,14 @@ __host__ __device__ constexpr int lds_pitch(int bk) { return bk + 4; }
 //   A step lies inside a single tap (r, s), so one table entry per step gives the tap's byte
 //   offset and mask bits, the channel offset is added on the scalar unit, and there are no
 //   padding rows.  Everything downstream of the staging registers is shared.
+// XL = 2 (a.xl = 3): activations [N][C][H][W] with C a multiple of every K-step, reduction rows
+//   ordered (r, s, c) as well: a step is BK channels of ONE tap, so the lane's masked offset is
+//   formed once per step instead of once per loaded element, and the channel stride H*W*4 goes
+//   into the scalar offset of each one-dword load.  fp32 MFMAs issue through the same port as every
+//   other vector ALU instruction (measured: each such instruction takes 4.4 cycles or more away from
+//   the matrix rate, whichever wave it comes from), so the three address instructions per loaded
+//   element of the XL = 0 form cost 10-15 % of the arithmetic time; this form has three per step.
+//   A pointwise (1x1) layer is the single-tap case of it.
 // The layout of y (and of a fused residual) is a run-time flag of the epilogue (a.yl).
 template <int BM, int BN, int BK, int WM, int WN, int PD, int XL>
 __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
@@ -170,8 +178,9 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
             int n = fdiv(m, a.div_pq), pq = m - n * a.PQ;
             int p = fdiv(pq, a.div_q), q = pq - p * a.Q;
             int ih0 = p * a.stride_h - a.pad_h, iw0 = q * a.stride_w - a.pad_w;
-            xvoff[i] = a.xl ? ((n * a.H + p * a.stride_h) * a.W + q * a.stride_w) * a.C * 4
-                            : ((n * a.C * a.H + p * a.stride_h) * a.W + q * a.stride_w) * 4;
+            // channels-last x: a.xl 1 or 2; [N][C][H][W]: 0 or 3
+            xvoff[i] = (a.xl == 1 || a.xl == 2) ? ((n * a.H + p * a.stride_h) * a.W + q * a.stride_w) * a.C * 4
+                                                : ((n * a.C * a.H + p * a.stride_h) * a.W + q * a.stride_w) * 4;
             unsigned inv = 0x80000000u;
             // rows below the image are r < -ih0, rows past it r >= H - ih0 when the dilation is 1:
             // two clamped shifts instead of a loop over the filter
@@ -206,7 +215,9 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     constexpr int NX = XP * XR;   // activation dwords per thread and tile
     constexpr int NXQ = NX / 4;   // ... stored to LDS as quads
     constexpr int NW = WL;        // weight quads per thread and tile
-    constexpr int NXL = XL ? NXQ : NX;  // activation load instructions per thread and tile
+    constexpr bool TAPM = XL != 0;      // a step lies inside one filter tap (reduction order (r, s, c))
+    constexpr bool QUAD = XL == 1;      // ... and a lane loads four channels at a time
+    constexpr int NXL = QUAD ? NXQ : NX;  // activation load instructions per thread and tile
     float xr[PD * NX];
     v4f wr[PD * NW];
     int tap_off[XR], tap_rs[XR];  // wave-uniform: live in scalar registers
@@ -223,18 +234,27 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     // table has one entry per tap, {byte offset of the tap, mask bits}, and tap_cbase carries
     // the channel offset.
     int tap_cbase = 0;  // channel base of the tile whose taps are loaded, added at the use
-    int tap_c0 = XL ? (kbeg * BK) / a.C : (kbeg * BK) / a.RS;
-    int tap_phase = XL ? kbeg * BK - tap_c0 * a.C : kbeg * BK - tap_c0 * a.RS;
-    auto load_taps = [&](int step) WPK_LAMBDA {
-        if constexpr (XL) {
+    int tap_c0 = TAPM ? (kbeg * BK) / a.C : (kbeg * BK) / a.RS;
+    int tap_phase = TAPM ? kbeg * BK - tap_c0 * a.C : kbeg * BK - tap_c0 * a.RS;
+    int xvb[XP];        // tap-major forms: the lane offset with the step's mask folded in
+    auto fold_mask = [&]() WPK_LAMBDA {
+        static_for<XP>([&](auto I) WPK_LAMBDA {
+            constexpr int i = decltype(I)::value;
+            xvb[i] = xvoff[i] | __builtin_amdgcn_sbfe((int)xinv[i], tap_rs[0] & 0xff, 1) |
+                     __builtin_amdgcn_sbfe((int)xinv[i], tap_rs[0] >> 8, 1);  // offset, or all ones
+        });
+    };
+    auto load_taps = [&](int step, bool fold = true) WPK_LAMBDA {
+        if constexpr (TAPM) {
             tap_off[0] = taps[2 * tap_c0];
             tap_rs[0] = taps[2 * tap_c0 + 1];
-            tap_cbase = (tap_phase + rg * XR) * 4;
+            tap_cbase = (tap_phase + rg * XR) * (QUAD ? 4 : a.HW4);
             tap_phase += BK;
             if (tap_phase >= a.C) {
                 tap_phase = 0;
                 tap_c0 += 1;
             }
+            if (fold) fold_mask();
             return;
         }
         const bool last = step == a.nsteps - 1;
@@ -255,18 +275,21 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     };
     // global -> register set SET: activation dword E of the tile whose taps are loaded
     auto load_x = [&](auto SET, auto E) WPK_LAMBDA {
-        if constexpr (XL) {  // E counts quads: pixel i, quad j4 of this thread's XR rows
+        if constexpr (QUAD) {  // E counts quads: pixel i, quad j4 of this thread's XR rows
             constexpr int set = decltype(SET)::value, e = decltype(E)::value;
             constexpr int i = e / (XR / 4), j4 = e % (XR / 4), b = set * NX + i * XR + 4 * j4;
-            int bad = __builtin_amdgcn_sbfe((int)xinv[i], tap_rs[0] & 0xff, 1) |
-                      __builtin_amdgcn_sbfe((int)xinv[i], tap_rs[0] >> 8, 1);  // 0 or all ones
             v4f v = __builtin_bit_cast(
-                v4f, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, xvoff[i] | bad,
-                                                           tap_off[0] + tap_cbase + 16 * j4, 0));
+                v4f, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, xvb[i], tap_off[0] + tap_cbase + 16 * j4, 0));
             xr[b] = v[0];
             xr[b + 1] = v[1];
             xr[b + 2] = v[2];
             xr[b + 3] = v[3];
+            return;
+        }
+        if constexpr (TAPM) {  // channel jj of this thread's XR, pixel i: the stride goes into the scalar offset
+            constexpr int set = decltype(SET)::value, e = decltype(E)::value, i = e / XR, jj = e % XR;
+            xr[set * NX + e] = __builtin_bit_cast(
+                float, __builtin_amdgcn_raw_buffer_load_b32(xrsrc, xvb[i], tap_off[0] + tap_cbase + jj * a.HW4, 0));
             return;
         }
         constexpr int set = decltype(SET)::value, e = decltype(E)::value, i = e / XR, jj = e % XR;
@@ -323,37 +346,54 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     constexpr int NIT = NXQ + NW + NXL + NW;       // stores (x, w) then loads (x, w)
     // the first load item must not come before the scalar tap loads it depends on
     static_assert(((NXQ + NW) * NM + NIT - 1) / NIT >= NNT * NMT, "taps are loaded too late");
+    // Pipelined form (K-steps of two octets or more): the operands of a step's FIRST octet are read
+    // during the step before it.  The step's only barrier sits in front of its last octet of
+    // MFMAs: by then every LDS store of tile r+1 has been issued (they ride behind the MFMAs of
+    // the octets before) and every wave holds the last operands of step r in registers, so right
+    // after the barrier the first octet of step r+1 is read from the other buffer and arrives
+    // while the last octet of step r is being multiplied.  A wave that has a SIMD to itself (the
+    // end of every launch, every launch of few workgroups) then never waits for LDS at a step's
+    // start; with one barrier-then-read per step that wait was a fifth of the step.
+    constexpr int NO = BK / 8;                      // octets per step
+    constexpr bool PIPE = NO >= 2;
+    constexpr int NML = 4 * NNT * NMT;              // MFMAs per octet
+    // every LDS store of the interleaved list rides behind an MFMA before the last octet
+    static_assert(!PIPE || ((NXQ + NW) * NM + NIT - 1) / NIT <= NM - NML, "LDS stores reach the last octet");
+    v4f av[2 * NNT], bv[2 * NMT];
+    auto read_octet = [&](const int buf, auto HALF, const int oct) WPK_LAMBDA {
+        constexpr int h = decltype(HALF)::value;
+        const float *xs = Xs0 + buf * XTILE + (wave_m * TM + lcol) * PX + lrow * 4 + oct * 8;
+        const float *ws = Ws0 + buf * WTILE + (wave_n * TN + lcol) * PW + lrow * 4 + oct * 8;
+        static_for<NNT>([&](auto I) WPK_LAMBDA {
+            av[h * NNT + decltype(I)::value] = *reinterpret_cast<const v4f *>(ws + decltype(I)::value * 32 * PW);
+        });
+        static_for<NMT>([&](auto J) WPK_LAMBDA {
+            bv[h * NMT + decltype(J)::value] = *reinterpret_cast<const v4f *>(xs + decltype(J)::value * 32 * PX);
+        });
+    };
     auto step_body = [&](const int r, auto SET, auto INTERLEAVE) WPK_LAMBDA {
         constexpr bool inter = decltype(INTERLEAVE)::value;
         const int cur = r & 1;
-        const float *xs = Xs0 + cur * XTILE + (wave_m * TM + lcol) * PX + lrow * 4;
-        const float *ws = Ws0 + cur * WTILE + (wave_n * TN + lcol) * PW + lrow * 4;
-        v4f av[2 * NNT], bv[2 * NMT];
-        static_for<NNT>([&](auto I) WPK_LAMBDA {
-            av[decltype(I)::value] = *reinterpret_cast<const v4f *>(ws + decltype(I)::value * 32 * PW);
-        });
-        static_for<NMT>([&](auto J) WPK_LAMBDA {
-            bv[decltype(J)::value] = *reinterpret_cast<const v4f *>(xs + decltype(J)::value * 32 * PX);
-        });
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<BK / 8>([&](auto KO) WPK_LAMBDA {
+        if constexpr (!PIPE) {
+            read_octet(cur, std::integral_constant<int, 0>{}, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        static_for<NO>([&](auto KO) WPK_LAMBDA {
             constexpr int ko = decltype(KO)::value;
             constexpr int c = ko & 1, nx = c ^ 1;
-            if constexpr (ko + 1 < BK / 8) {
-                static_for<NNT>([&](auto I) WPK_LAMBDA {
-                    av[nx * NNT + decltype(I)::value] = *reinterpret_cast<const v4f *>(
-                        ws + decltype(I)::value * 32 * PW + (ko + 1) * 8);
-                });
-                static_for<NMT>([&](auto J) WPK_LAMBDA {
-                    bv[nx * NMT + decltype(J)::value] = *reinterpret_cast<const v4f *>(
-                        xs + decltype(J)::value * 32 * PX + (ko + 1) * 8);
-                });
+            if constexpr (ko + 1 < NO) {
+                read_octet(cur, std::integral_constant<int, nx>{}, ko + 1);
+                __builtin_amdgcn_sched_barrier(0);
+            } else if constexpr (PIPE) {
+                __syncthreads();
+                // (after the last step of a segment this reads a tile nobody uses: in bounds, ignored)
+                read_octet(cur ^ 1, std::integral_constant<int, nx>{}, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            static_for<4 * NNT * NMT>([&](auto QIJ) WPK_LAMBDA {
+            static_for<NML>([&](auto QIJ) WPK_LAMBDA {
                 constexpr int qij = decltype(QIJ)::value;
                 constexpr int q = qij / (NNT * NMT), ij = qij % (NNT * NMT), i = ij / NMT, j = ij % NMT;
-                constexpr int t = ko * 4 * NNT * NMT + qij;  // number of this MFMA within the step
+                constexpr int t = ko * NML + qij;  // number of this MFMA within the step
                 acc[ij] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[c * NNT + i][q], bv[c * NMT + j][q],
                                                                acc[ij], 0, 0, 0);
                 if constexpr (inter) {
@@ -383,7 +423,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                 __builtin_amdgcn_sched_barrier(0);
             });
         });
-        __syncthreads();
+        if constexpr (!PIPE) __syncthreads();
     };
     using std::false_type;
     using std::true_type;
@@ -393,9 +433,10 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     // (tile 0: the scalar tap loads and the weight loads, which depend on the tile alone, are
     // issued first; the per-pixel gather state is computed while they are in flight)
     const int nr = kend - kbeg;
-    load_taps(kbeg);
+    load_taps(kbeg, false);
     static_for<NW>([&](auto E) WPK_LAMBDA { load_w(std::integral_constant<int, 0>{}, kbeg, E); });
     gather_state();
+    if constexpr (TAPM) fold_mask();
     static_for<NXL>([&](auto E) WPK_LAMBDA { load_x(std::integral_constant<int, 0>{}, E); });
     static_for<PD - 1>([&](auto P) WPK_LAMBDA {
         constexpr int t = decltype(P)::value + 1;
@@ -404,6 +445,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     store_tile(std::integral_constant<int, 0>{}, 0);
     if (PD < nr) load_tile(std::integral_constant<int, 0>{}, kbeg + PD);
     __syncthreads();
+    if constexpr (PIPE) read_octet(0, std::integral_constant<int, 0>{}, 0);
     int r = 0;
     // main loop: every step still has a tile to store (r+1) and one to load (r+1+PD)
     for (; r + 2 * PD < nr; r += PD)
@@ -454,11 +496,14 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
         if (tid == 0) a.ws_cnt[fix_j] = 0;        // leave the counter clean for the next launch
         // Add the other workgroups' slots to this one's accumulators.
         if constexpr (NNT * NMT == 1) {
-            // a single 32x32 block per wave has little to load per slot: two slots at a time (a
-            // slot number past the last becomes an out-of-range offset, which loads 0)
-            for (int t0 = 0; t0 < fix_n - 1; t0 += 2) {
-                v4f part[2][4];
-                static_for<2>([&](auto U) WPK_LAMBDA {
+            // a single 32x32 block per wave has little to load per slot: four slots at a time, all
+            // requested before the first is added, so the sharers of a tile cost one memory round
+            // trip per four of them (a slot number past the last becomes an out-of-range offset,
+            // which loads 0)
+            constexpr int kGang = 4;
+            for (int t0 = 0; t0 < fix_n - 1; t0 += kGang) {
+                v4f part[kGang][4];
+                static_for<kGang>([&](auto U) WPK_LAMBDA {
                     constexpr int u = decltype(U)::value;
                     const int t = t0 + u, sl = t + (t >= fix_slot ? 1 : 0);  // t-th slot not mine
                     const unsigned off =
@@ -469,7 +514,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                             v4f, __builtin_amdgcn_raw_buffer_load_b128(srsrc, off, qd * 16 * T, kCoherent));
                     });
                 });
-                static_for<8>([&](auto UQ) WPK_LAMBDA {
+                static_for<4 * kGang>([&](auto UQ) WPK_LAMBDA {
                     constexpr int u = decltype(UQ)::value / 4, qd = decltype(UQ)::value % 4;
                     acc[0][4 * qd] += part[u][qd][0];
                     acc[0][4 * qd + 1] += part[u][qd][1];
@@ -626,11 +671,12 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     // ---- which segments this workgroup runs ----------------------------------------------------
     // persist == 0: one workgroup per (tile, reduction slice): blockIdx -> tile, slice; the slices
     //   of a tile meet through the workspace if the host gave one, else through atomics.
-    // persist  > 0: gridDim.x = G persistent workgroups.  Each first takes whole tiles g, g+G, ...
+    // persist  > 0: gridDim.x = G persistent workgroups.  Each takes whole tiles g, g+G, ...
     //   of the first tiles_dp = floor(tiles/G)*G tiles.  The reduction steps of the remaining
     //   tiles, laid end to end (`units` of them), are cut into runs of q or q+1 steps (the first
     //   `rem` get q+1), one for each of the first sk_groups workgroups: all G of them, unless
-    //   that would make the runs too short to be worth a prologue.  A run that does
+    //   that would make the runs too short to be worth a prologue; a workgroup does its run first,
+    //   then its whole tiles.  A run that does
     //   not cover a tile's whole reduction shares the tile with its neighbours in g: fix-up
     //   through the workspace if the host gave one, else atomics into zeroed y.
     // (tiles_dp, sk_groups, q = sk_q, rem = sk_rem and the divisors come from the host: they
@@ -665,12 +711,10 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                 fix_slot = slice;
                 fix_n = a.split_k;
             }
-        } else if (persistent && next_dp < tiles_dp) {
-            tile = next_dp;
-            kbeg = 0;
-            kend = a.nsteps;
-            next_dp += G;
         } else if (persistent && u0 < u1) {
+            // (the dealt-out run comes BEFORE the workgroup's whole tiles: the sharers of a tile then
+            // meet while everybody else still has whole tiles to multiply, instead of after it, when
+            // the chain of memory round trips of the meeting would be all the device has left to do)
             fix_j = fdiv(u0, a.div_nsteps);
             tile = tiles_dp + fix_j;
             kbeg = u0 - fix_j * a.nsteps;
@@ -682,6 +726,13 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                 fix_slot = g - first;
                 mode = a.ws ? kFixup : kAtomic;
             }
+        } else if (persistent && next_dp < tiles_dp) {
+            // (remap: within a round, each XCD takes a contiguous range of the round's G tiles, so
+            // that tiles which share rows of x share an L2)
+            tile = a.remap ? next_dp - g + xcd_remap(g, G) : next_dp;
+            kbeg = 0;
+            kend = a.nsteps;
+            next_dp += G;
         } else {
             break;
         }
@@ -695,6 +746,8 @@ hipError_t launch_igemm(const IgemmArgs &a, hipStream_t stream)
     dim3 grid((unsigned)(a.persist > 0 ? a.grid_persist : a.tiles_m * a.tiles_n * a.split_k));
     if (a.xl == 2)
         hipLaunchKernelGGL((igemm_kernel<BM, BN, BK, WM, WN, PD, 1>), grid, dim3(64 * WM * WN), 0, stream, a);
+    else if (a.xl == 3)
+        hipLaunchKernelGGL((igemm_kernel<BM, BN, BK, WM, WN, PD, 2>), grid, dim3(64 * WM * WN), 0, stream, a);
     else
         hipLaunchKernelGGL((igemm_kernel<BM, BN, BK, WM, WN, PD, 0>), grid, dim3(64 * WM * WN), 0, stream, a);
     return hipGetLastError();

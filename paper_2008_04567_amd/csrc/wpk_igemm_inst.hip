@@ -44,6 +44,6 @@ namespace wpk {
 #define WPK_SEL_7 WPK_EMIT
 #endif
 #define WPK_VARIANT(PART, BM, BN, BK, WM, WN, PD) WPK_SEL_##PART(BM, BN, BK, WM, WN, PD)
-#include "wpk_variants.def"
+#include WPK_VARIANTS_FILE
 #undef WPK_VARIANT
 }  // namespace wpk

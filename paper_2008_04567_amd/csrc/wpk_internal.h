@@ -10,6 +10,12 @@
 
 #include "wpk.h"
 
+// The list of compiled tile combinations; a build may name a shorter list of its own (the gene
+// space shrinks with it: the constraint check only admits combinations on the list).
+#ifndef WPK_VARIANTS_FILE
+#define WPK_VARIANTS_FILE "wpk_variants.def"
+#endif
+
 namespace wpk {
 
 // ---- gene value lists (the search sees index ranges into them) -------------------------------
@@ -65,6 +71,7 @@ struct Problem {
     bool tiled_ok;   // the tiled family can run it (else only the direct kernel)
     bool xl, yl;     // x / y channels-last (bits 0 and 1 of the descriptor's layout)
     bool xquad;      // channels-last x gathered as 16-byte channel quads (C a multiple of every K-step)
+    bool tapmajor;   // x [N][C][H][W] with C a multiple of every K-step: reduction ordered (r, s, c) as well
 };
 int make_problem(const wpk_conv_desc *d, Problem *out);  // WPK_OK or a WPK_E_* code
 std::string desc_key(const wpk_conv_desc *d);
@@ -137,7 +144,8 @@ struct IgemmArgs {
     FastDiv div_pq, div_q, div_tiles_n, div_tiles, div_nsteps, div_q1, div_q0;  // by PQ, Q, tiles_n,
                         // tiles, nsteps, sk_q + 1, max(sk_q, 1)
     int32_t xl;         // 0: x is [N][C][H][W]; 1: channels-last, gathered row by row; 2: channels-last,
-                        // gathered as 16-byte channel quads (reduction rows ordered (r, s, c))
+                        // gathered as 16-byte channel quads (reduction rows ordered (r, s, c)); 3: [N][C][H][W]
+                        // with the reduction ordered (r, s, c), one filter tap per step
     int32_t yl;         // 1: y (and the residual) are channels-last; 2: also K % 4 == 0 and y, residual and
                         // bias 16-byte aligned, so a pixel's channel quads move as 16-byte accesses
 };
