@@ -521,6 +521,7 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     a.div_nsteps = make_fastdiv((uint32_t)a.nsteps);
     a.div_q1 = make_fastdiv((uint32_t)a.sk_q + 1);
     a.div_q0 = make_fastdiv((uint32_t)std::max(a.sk_q, 1));
+    a.div_tap = make_fastdiv((uint32_t)(pr.xquad || pr.tapmajor ? d.c : a.RS));
     a.ws = nullptr;
     a.ws_cnt = nullptr;
     a.ws_maxc = 0;

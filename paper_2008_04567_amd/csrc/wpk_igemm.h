@@ -79,6 +79,21 @@ __device__ __forceinline__ int fdiv(int n, const FastDiv &f)
 // 0.8 us per launch on a layer that writes 12.8 MB, nothing on small outputs.
 constexpr int kYStorePolicy = 17;
 
+// Arguments that only a segment's set-up, its epilogue or the work iterator use are read from the
+// kernel-argument segment at the place of use (scalar loads that hit the scalar cache) instead of
+// being held in scalar registers from the kernel's entry on: together with everything the compiler
+// derives from them ahead of the segment loop they overflowed the scalar register file, and every
+// spilled value is a vector ALU instruction at the spill and at each reload, which the matrix pipe
+// pays for.  The empty asm statement hides the pointer's origin, so the loads stay where they are.
+typedef const IgemmArgs __attribute__((address_space(4))) *cold_ptr;
+#define WPK_COLD_DIV(c, f) (FastDiv{(c)->f.mul, (c)->f.sh})
+__device__ __forceinline__ cold_ptr cold_args()
+{
+    unsigned long long p = (unsigned long long)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(p));
+    return (cold_ptr)p;
+}
+
 // The tap table is read through the constant address space: wave-uniform scalar loads.
 typedef const int __attribute__((address_space(4))) *tap_ptr;
 
@@ -158,7 +173,12 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     auto run_segment = [&](const int tile, const int kbeg, const int kend, const int mode,
                            const int fix_j, const int fix_slot, const int fix_n) WPK_LAMBDA {
     if (kbeg >= kend) return;  // nothing to reduce: touch neither the tap table nor y
-    const int tile_m = fdiv(tile, a.div_tiles_n), tile_n = tile - tile_m * a.tiles_n;
+    int tile_m, tile_n;
+    {
+        const cold_ptr c = cold_args();
+        tile_m = fdiv(tile, WPK_COLD_DIV(c, div_tiles_n));
+        tile_n = tile - tile_m * c->tiles_n;
+    }
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     // ---- per-thread gather state ---------------------------------------------------------------
@@ -169,18 +189,19 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     int xvoff[XP];
     unsigned xinv[XP];
     auto gather_state = [&]() WPK_LAMBDA {
+    const cold_ptr c = cold_args();
     static_for<XP>([&](auto I) WPK_LAMBDA {
         constexpr int i = decltype(I)::value;
         int m = m0 + pm0 + i * T;
         xvoff[i] = 0;
         xinv[i] = 0xffffffffu;
-        if (m < a.M) {
-            int n = fdiv(m, a.div_pq), pq = m - n * a.PQ;
-            int p = fdiv(pq, a.div_q), q = pq - p * a.Q;
-            int ih0 = p * a.stride_h - a.pad_h, iw0 = q * a.stride_w - a.pad_w;
-            // channels-last x: a.xl 1 or 2; [N][C][H][W]: 0 or 3
-            xvoff[i] = (a.xl == 1 || a.xl == 2) ? ((n * a.H + p * a.stride_h) * a.W + q * a.stride_w) * a.C * 4
-                                                : ((n * a.C * a.H + p * a.stride_h) * a.W + q * a.stride_w) * 4;
+        if (m < c->M) {
+            int n = fdiv(m, WPK_COLD_DIV(c, div_pq)), pq = m - n * c->PQ;
+            int p = fdiv(pq, WPK_COLD_DIV(c, div_q)), q = pq - p * c->Q;
+            int ih0 = p * c->stride_h - c->pad_h, iw0 = q * c->stride_w - c->pad_w;
+            // channels-last x: c->xl 1 or 2; [N][C][H][W]: 0 or 3
+            xvoff[i] = (c->xl == 1 || c->xl == 2) ? ((n * c->H + p * c->stride_h) * c->W + q * c->stride_w) * c->C * 4
+                                                : ((n * c->C * c->H + p * c->stride_h) * c->W + q * c->stride_w) * 4;
             unsigned inv = 0x80000000u;
             // rows below the image are r < -ih0, rows past it r >= H - ih0 when the dilation is 1:
             // two clamped shifts instead of a loop over the filter
@@ -188,20 +209,20 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                 const int lo = min(max(-o0, 0), taps), hi = min(max(len - o0, 0), taps);
                 return ((1u << lo) - 1u) | (((1u << taps) - 1u) & ~((1u << hi) - 1u));
             };
-            if (a.dil_h == 1) {
-                inv |= outside(ih0, a.H, a.R);
+            if (c->dil_h == 1) {
+                inv |= outside(ih0, c->H, c->R);
             } else {
-                for (int r = 0; r < a.R; ++r) {
-                    int ih = ih0 + r * a.dil_h;
-                    if (ih < 0 || ih >= a.H) inv |= 1u << r;
+                for (int r = 0; r < c->R; ++r) {
+                    int ih = ih0 + r * c->dil_h;
+                    if (ih < 0 || ih >= c->H) inv |= 1u << r;
                 }
             }
-            if (a.dil_w == 1) {
-                inv |= outside(iw0, a.W, a.S) << 16;
+            if (c->dil_w == 1) {
+                inv |= outside(iw0, c->W, c->S) << 16;
             } else {
-                for (int sx = 0; sx < a.S; ++sx) {
-                    int iw = iw0 + sx * a.dil_w;
-                    if (iw < 0 || iw >= a.W) inv |= 1u << (16 + sx);
+                for (int sx = 0; sx < c->S; ++sx) {
+                    int iw = iw0 + sx * c->dil_w;
+                    if (iw < 0 || iw >= c->W) inv |= 1u << (16 + sx);
                 }
             }
             xinv[i] = inv;
@@ -234,7 +255,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     // table has one entry per tap, {byte offset of the tap, mask bits}, and tap_cbase carries
     // the channel offset.
     int tap_cbase = 0;  // channel base of the tile whose taps are loaded, added at the use
-    int tap_c0 = TAPM ? (kbeg * BK) / a.C : (kbeg * BK) / a.RS;
+    int tap_c0 = fdiv(kbeg * BK, WPK_COLD_DIV(cold_args(), div_tap));  // by C (tap-major forms) or R*S
     int tap_phase = TAPM ? kbeg * BK - tap_c0 * a.C : kbeg * BK - tap_c0 * a.RS;
     int xvb[XP];        // tap-major forms: the lane offset with the step's mask folded in
     auto fold_mask = [&]() WPK_LAMBDA {
@@ -465,6 +486,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
         step_body(r, std::integral_constant<int, 0>{}, false_type{});
     }
 
+    const cold_ptr ce = cold_args();  // (after the steps: what the meeting and the stores need)
     // ---- fix-up of a shared tile -----------------------------------------------------------------
     if (mode == kFixup) {
         // Slot layout: accumulator quad (ij, e4) of thread t at float (ij*4 + e4)*4*T + 4*t.
@@ -474,7 +496,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
         // through / read past the non-coherent levels); everything else stays cached.
         constexpr int kCoherent = 17;  // sc0 | sc1
         const __amdgpu_buffer_rsrc_t srsrc = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)(a.ws + (size_t)fix_j * a.ws_maxc * (BM * BN)), 0, a.ws_maxc * (BM * BN) * 4,
+            (void *)(ce->ws + (size_t)fix_j * ce->ws_maxc * (BM * BN)), 0, ce->ws_maxc * (BM * BN) * 4,
             0x00020000);
         const int mine = (fix_slot * (BM * BN) + 4 * tid) * 4;
         static_for<NNT * NMT * 4>([&](auto Q) WPK_LAMBDA {
@@ -488,12 +510,12 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (tid == 0) arrival = atomicAdd(a.ws_cnt + fix_j, 1);
+        if (tid == 0) arrival = atomicAdd(ce->ws_cnt + fix_j, 1);
         __syncthreads();
         const int arrived_before = arrival;
         __syncthreads();  // everyone has read `arrival` before a later segment overwrites it
         if (arrived_before != fix_n - 1) return;  // not the last: done with this tile
-        if (tid == 0) a.ws_cnt[fix_j] = 0;        // leave the counter clean for the next launch
+        if (tid == 0) ce->ws_cnt[fix_j] = 0;        // leave the counter clean for the next launch
         // Add the other workgroups' slots to this one's accumulators.
         if constexpr (NNT * NMT == 1) {
             // a single 32x32 block per wave has little to load per slot: four slots at a time, all
@@ -540,7 +562,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     }
     const bool atomic = mode == kAtomic;
     // the host applies the epilogue itself after a launch that accumulates with atomics
-    const bool fused = !atomic && (a.bias || a.res || a.relu);
+    const bool fused = !atomic && (ce->bias || ce->res || ce->relu);
 
     // ---- epilogue: D[row = channel][col = pixel]; register e of lane l holds row
     //      8*(e/4) + 4*(l/32) + e%4 and column l%32 of its 32x32 block.  Buffer addressing: one
@@ -548,21 +570,21 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     //      64-bit address per output.  A NULL bias or residual becomes a buffer of zero records,
     //      whose loads return 0. ------------------------------------------------------------------
     const __amdgpu_buffer_rsrc_t yrsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void *)a.y, 0, (int)a.y_bytes, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void *)ce->y, 0, (int)ce->y_bytes, 0x00020000);
     // y[n][k][p][q]: consecutive channels are PQ elements apart; channels-last y[n][p][q][k]: 1
-    const int PQ4 = a.yl ? 4 : a.PQ * 4;
+    const int PQ4 = ce->yl ? 4 : ce->PQ * 4;
     static_for<NMT>([&](auto J) WPK_LAMBDA {
         constexpr int j = decltype(J)::value;
         int m = m0 + wave_m * TM + j * 32 + lcol;
-        if (m < a.M) {
-            int n = fdiv(m, a.div_pq), pq = m - n * a.PQ;
+        if (m < ce->M) {
+            int n = fdiv(m, WPK_COLD_DIV(ce, div_pq)), pq = m - n * ce->PQ;
             static_for<NNT>([&](auto I) WPK_LAMBDA {
                 constexpr int i = decltype(I)::value;
                 const int kbase = n0 + wave_n * TN + i * 32 + 4 * lrow;  // + 8*(e/4) + e%4
                 // byte offset of (n, kbase, pq) in y; only used for channels below K, where it
                 // is below y_bytes < 2^32
-                const unsigned voff = a.yl ? (unsigned)(((size_t)m * a.K + kbase) * 4)
-                                           : (unsigned)((((size_t)n * a.K + kbase) * a.PQ + pq) * 4);
+                const unsigned voff = ce->yl ? (unsigned)(((size_t)m * ce->K + kbase) * 4)
+                                           : (unsigned)((((size_t)n * ce->K + kbase) * ce->PQ + pq) * 4);
                 // A 32-channel block that lies wholly below K (the usual case) stores without a
                 // bound check per register; the check costs an exec-mask round trip each.
                 auto emit = [&](auto FULL, auto THROUGH) WPK_LAMBDA {
@@ -570,32 +592,32 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                     // channels-last outputs leave a lane in 16-byte pieces that only the L2 merges
                     // into whole lines: they keep the default write-back policy
                     constexpr int policy = decltype(THROUGH)::value ? kYStorePolicy : 0;
-                    if (a.yl == 2 && !atomic) {
+                    if (ce->yl == 2 && !atomic) {
                         // channels-last y with K a multiple of 4 and 16-byte aligned tensors: the four
                         // registers 4g..4g+3 of a lane are four consecutive channels of its pixel
                         const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
-                            (void *)(a.bias ? a.bias : a.y), 0, a.bias ? a.K * 4 : 0, 0x00020000);
+                            (void *)(ce->bias ? ce->bias : ce->y), 0, ce->bias ? ce->K * 4 : 0, 0x00020000);
                         const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
-                            (void *)(a.res ? a.res : a.y), 0, a.res ? (int)a.y_bytes : 0, 0x00020000);
+                            (void *)(ce->res ? ce->res : ce->y), 0, ce->res ? (int)ce->y_bytes : 0, 0x00020000);
                         v4f add[4];
                         if (fused)
                             static_for<4>([&](auto G) WPK_LAMBDA {
                                 constexpr int g = decltype(G)::value;
                                 v4f t = __builtin_bit_cast(
                                     v4f, __builtin_amdgcn_raw_buffer_load_b128(brsrc, kbase * 4, 32 * g, 0));
-                                if (full || kbase + 8 * g < a.K)
+                                if (full || kbase + 8 * g < ce->K)
                                     t += __builtin_bit_cast(
                                         v4f, __builtin_amdgcn_raw_buffer_load_b128(rrsrc, voff, 32 * g, 0));
                                 add[g] = t;
                             });
                         static_for<4>([&](auto G) WPK_LAMBDA {
                             constexpr int g = decltype(G)::value;
-                            if (full || kbase + 8 * g < a.K) {
+                            if (full || kbase + 8 * g < ce->K) {
                                 v4f v = {acc[i * NMT + j][4 * g], acc[i * NMT + j][4 * g + 1],
                                          acc[i * NMT + j][4 * g + 2], acc[i * NMT + j][4 * g + 3]};
                                 if (fused) {
                                     v += add[g];
-                                    if (a.relu)
+                                    if (ce->relu)
                                         v = (v4f){fmaxf(v[0], 0.0f), fmaxf(v[1], 0.0f), fmaxf(v[2], 0.0f),
                                                   fmaxf(v[3], 0.0f)};
                                 }
@@ -605,9 +627,9 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                         });
                     } else if (fused) {
                         const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
-                            (void *)(a.bias ? a.bias : a.y), 0, a.bias ? a.K * 4 : 0, 0x00020000);
+                            (void *)(ce->bias ? ce->bias : ce->y), 0, ce->bias ? ce->K * 4 : 0, 0x00020000);
                         const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
-                            (void *)(a.res ? a.res : a.y), 0, a.res ? (int)a.y_bytes : 0, 0x00020000);
+                            (void *)(ce->res ? ce->res : ce->y), 0, ce->res ? (int)ce->y_bytes : 0, 0x00020000);
                         // everything the 16 outputs of this block add is fetched first, so the loads
                         // are all in flight together; then the stores
                         float add[16];
@@ -615,16 +637,16 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                             constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
                             float t = __builtin_bit_cast(
                                 float, __builtin_amdgcn_raw_buffer_load_b32(brsrc, kbase * 4, de * 4, 0));
-                            if (full || kbase + de < a.K)
+                            if (full || kbase + de < ce->K)
                                 t += __builtin_bit_cast(
                                     float, __builtin_amdgcn_raw_buffer_load_b32(rrsrc, voff, de * PQ4, 0));
                             add[e] = t;
                         });
                         static_for<16>([&](auto E) WPK_LAMBDA {
                             constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
-                            if (full || kbase + de < a.K) {
+                            if (full || kbase + de < ce->K) {
                                 float v = acc[i * NMT + j][e] + add[e];
-                                v = a.relu ? fmaxf(v, 0.0f) : v;
+                                v = ce->relu ? fmaxf(v, 0.0f) : v;
                                 __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
                                                                       voff, de * PQ4, policy);
                             }
@@ -633,7 +655,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                         // (no-return fp32 adds, addressed like the stores)
                         static_for<16>([&](auto E) WPK_LAMBDA {
                             constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
-                            if (full || kbase + de < a.K) {
+                            if (full || kbase + de < ce->K) {
                                 const float v = acc[i * NMT + j][e];
                                 __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(v, yrsrc, voff, de * PQ4, 0);
                             }
@@ -641,7 +663,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                     } else {
                         static_for<16>([&](auto E) WPK_LAMBDA {
                             constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
-                            if (full || kbase + de < a.K) {
+                            if (full || kbase + de < ce->K) {
                                 // a copy first: a bit cast taken straight from a vector element
                                 // reads element 0 with this compiler
                                 const float v = acc[i * NMT + j][e];
@@ -651,8 +673,8 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
                         });
                     }
                 };
-                const bool whole = n0 + wave_n * TN + i * 32 + 32 <= a.K;
-                if (a.yl == 0) {
+                const bool whole = n0 + wave_n * TN + i * 32 + 32 <= ce->K;
+                if (ce->yl == 0) {
                     if (whole)
                         emit(std::true_type{}, std::true_type{});
                     else
@@ -681,55 +703,60 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     //   through the workspace if the host gave one, else atomics into zeroed y.
     // (tiles_dp, sk_groups, q = sk_q, rem = sk_rem and the divisors come from the host: they
     // depend on the launch alone, and all of it fits 32 bits)
-    const int tiles = a.tiles;
     const bool persistent = a.persist > 0;
     const int G = gridDim.x, g = blockIdx.x;
-    const int tiles_dp = a.tiles_dp;
-    const int q = a.sk_q, rem = a.sk_rem;
-    auto run_start = [&](int gg) { return gg * q + (gg < rem ? gg : rem); };
-    auto owner_of = [&](int u) {  // which workgroup's run holds unit u
-        if (u < rem * (q + 1)) return fdiv(u, a.div_q1);
-        return rem + fdiv(u - rem * (q + 1), a.div_q0);
-    };
     int next_dp = g;
-    const bool dealt = persistent && g < a.sk_groups;
-    int u0 = dealt ? run_start(g) : 0;
-    const int u1 = dealt ? run_start(g + 1) : 0;
+    // (remap: run number gr instead of g, so that consecutive runs -- neighbouring tiles, the
+    // slices of one tile -- sit on one XCD and share its L2)
+    const int gr = a.remap ? xcd_remap(g, G) : g;
+    int u0, u1;
+    {
+        const cold_ptr c = cold_args();
+        const int q = c->sk_q, rem = c->sk_rem;
+        const bool dealt = persistent && gr < c->sk_groups;
+        u0 = dealt ? gr * q + min(gr, rem) : 0;
+        u1 = dealt ? (gr + 1) * q + min(gr + 1, rem) : 0;
+    }
     bool once = !persistent;
     for (;;) {
         int tile, kbeg, kend, mode = kStore, fix_j = 0, fix_slot = 0, fix_n = 1;
+        const cold_ptr c = cold_args();   // the iterator's constants, once per segment
         if (once) {
             once = false;
-            int bid = a.remap ? xcd_remap(g, G) : g;
-            const int slice = fdiv(bid, a.div_tiles);
-            tile = bid - slice * tiles;
-            kbeg = slice * a.steps_per_split;
-            kend = min(a.nsteps, kbeg + a.steps_per_split);
-            if (a.split_k > 1) {
-                mode = a.ws ? kFixup : kAtomic;
+            const int slice = fdiv(gr, WPK_COLD_DIV(c, div_tiles));
+            tile = gr - slice * c->tiles;
+            kbeg = slice * c->steps_per_split;
+            kend = min(a.nsteps, kbeg + c->steps_per_split);
+            if (c->split_k > 1) {
+                mode = c->ws ? kFixup : kAtomic;
                 fix_j = tile;
                 fix_slot = slice;
-                fix_n = a.split_k;
+                fix_n = c->split_k;
             }
         } else if (persistent && u0 < u1) {
             // (the dealt-out run comes BEFORE the workgroup's whole tiles: the sharers of a tile then
             // meet while everybody else still has whole tiles to multiply, instead of after it, when
             // the chain of memory round trips of the meeting would be all the device has left to do)
-            fix_j = fdiv(u0, a.div_nsteps);
-            tile = tiles_dp + fix_j;
+            const int q = c->sk_q, rem = c->sk_rem;
+            auto owner_of = [&](int u) {  // which workgroup's run holds unit u
+                if (u < rem * (q + 1)) return fdiv(u, WPK_COLD_DIV(c, div_q1));
+                return rem + fdiv(u - rem * (q + 1), WPK_COLD_DIV(c, div_q0));
+            };
+            fix_j = fdiv(u0, WPK_COLD_DIV(c, div_nsteps));
+            tile = c->tiles_dp + fix_j;
             kbeg = u0 - fix_j * a.nsteps;
             kend = min(a.nsteps, kbeg + (u1 - u0));
             u0 += kend - kbeg;
             if (!(kbeg == 0 && kend == a.nsteps)) {
                 const int first = owner_of(fix_j * a.nsteps);
                 fix_n = owner_of((fix_j + 1) * a.nsteps - 1) - first + 1;
-                fix_slot = g - first;
-                mode = a.ws ? kFixup : kAtomic;
+                fix_slot = gr - first;
+                mode = c->ws ? kFixup : kAtomic;
             }
-        } else if (persistent && next_dp < tiles_dp) {
+        } else if (persistent && next_dp < c->tiles_dp) {
             // (remap: within a round, each XCD takes a contiguous range of the round's G tiles, so
             // that tiles which share rows of x share an L2)
-            tile = a.remap ? next_dp - g + xcd_remap(g, G) : next_dp;
+            tile = next_dp - g + gr;
             kbeg = 0;
             kend = a.nsteps;
             next_dp += G;

@@ -143,6 +143,8 @@ struct IgemmArgs {
     int32_t sk_q, sk_rem;  // in runs of sk_q steps (+1 for the first sk_rem)
     FastDiv div_pq, div_q, div_tiles_n, div_tiles, div_nsteps, div_q1, div_q0;  // by PQ, Q, tiles_n,
                         // tiles, nsteps, sk_q + 1, max(sk_q, 1)
+    FastDiv div_tap;    // by what a reduction row index is divided to find its first table entry: C where a
+                        // K-step lies inside one filter tap, else R*S
     int32_t xl;         // 0: x is [N][C][H][W]; 1: channels-last, gathered row by row; 2: channels-last,
                         // gathered as 16-byte channel quads (reduction rows ordered (r, s, c)); 3: [N][C][H][W]
                         // with the reduction ordered (r, s, c), one filter tap per step
