@@ -95,7 +95,7 @@ int wpk_last_hip_error(void);
  * wpk_config_legal() says so (the constraint check of Step1): the tile combination must be one
  * the library was built with, its LDS and workgroup size must fit a gfx950 compute unit,
  * split_k may not exceed the number of reduction steps, and the persistent schedule excludes
- * split_k > 1.
+ * split_k > 1 and always has xcd_remap = 1.
  */
 #define WPK_N_GENES 10
 typedef struct wpk_conv_config {

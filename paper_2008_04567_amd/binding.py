@@ -173,7 +173,7 @@ def make_desc(layer=None, **kw):
 
 
 def make_config(bm, bn, bk, wm, wn, split_k=1, xcd_remap=1, persist=0, stages=2, reduce=0):
-    return ConvConfig(bm, bn, bk, wm, wn, split_k, 0 if persist else xcd_remap, persist, stages, reduce)
+    return ConvConfig(bm, bn, bk, wm, wn, split_k, 1 if persist else xcd_remap, persist, stages, reduce)
 
 
 def _ptr(t):

@@ -1155,12 +1155,9 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int
                 wpk_conv_config c = {sh[0], sh[1], sh[2], sh[3], sh[4], 1, 0, 0, sh[5], 0};
                 for (int p = 2; p <= 4; ++p) {
                     c.persist = p;
-                    for (int remap = 0; remap < 2; ++remap) {
-                        c.xcd_remap = remap;
-                        c.reduce = 0;
-                        consider(c);
-                    }
-                    c.xcd_remap = 0;
+                    c.xcd_remap = 1;
+                    c.reduce = 0;
+                    consider(c);
                     c.reduce = 1;
                     consider(c);
                 }

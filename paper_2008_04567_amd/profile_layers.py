@@ -3,7 +3,8 @@
     rocprofv3 --kernel-trace --stats -- python3 -m paper_2008_04567_amd.profile_layers \
         --workload config3 --cache tuned.cache --reps 20 --manifest order.json
 
-With ``--cache`` the layers run under the configurations a search stored there (``--tune`` searches
+``--config LAYER=...`` pins a layer's configuration.  With ``--cache`` the layers run under the
+configurations a search stored there (``--tune`` searches
 the missing ones first and saves them: do that in a run of its own, outside the profiler); without
 it under the library's defaults.  The manifest lists the convolution launches in order -- layer,
 configuration, kernel name, grid size, algorithmic bytes and FLOPs -- so that a per-dispatch
@@ -39,6 +40,11 @@ def main():
     ap.add_argument("--warm", type=int, default=2, help="launches per layer before the counted ones (also listed)")
     ap.add_argument("--unique", action="store_true", help="each distinct shape once")
     ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc"])
+    ap.add_argument("--config", action="append", default=[], metavar="LAYER=bm,bn,bk,wm,wn,split,remap,persist,stages,reduce",
+                    help="run the named layer under this configuration instead (may be repeated)")
+    ap.add_argument("--sweep", default=None, metavar="FILE",
+                    help="text file of lines 'LAYER bm,bn,bk,wm,wn,split,remap,persist,stages,reduce': run exactly "
+                         "these (layer, configuration) pairs, in the file's order, instead of every layer once")
     ap.add_argument("--manifest", default=None)
     ap.add_argument("--calibrate-copy", action="store_true")
     args = ap.parse_args()
@@ -67,16 +73,37 @@ def main():
         if args.cache:
             B.cache_save(args.cache)
     plan = B.Plan(descs, tune=False)
+    forced = dict(c.split("=", 1) for c in args.config)
+    for i, l in enumerate(layers):
+        if l["name"] in forced:
+            plan.set_layer_config(i, B.ConvConfig(*[int(v) for v in forced[l["name"]].split(",")]))
     stream = torch.cuda.current_stream()
     order = []
-    for i, (l, d) in enumerate(zip(layers, descs)):
-        x, w = W.make_inputs(l)
-        if layout & 1:
-            x = x.transpose(0, 2, 3, 1).copy()
-        P, Q = B.conv_out_shape(d)
-        xd, wd = torch.from_numpy(x).to(dev), torch.from_numpy(w).to(dev)
-        yd = torch.empty(l["n"] * l["k"] * P * Q, device=dev, dtype=torch.float32)
-        plan.set_weights(i, wd)
+    runs = [(i, None) for i in range(len(layers))]
+    if args.sweep:
+        index = {l["name"]: i for i, l in enumerate(layers)}
+        runs = []
+        for line in open(args.sweep):
+            t = line.split()
+            if len(t) == 2 and not line.startswith("#"):
+                cfg = B.ConvConfig(*[int(v) for v in t[1].split(",")])
+                if B.config_legal(descs[index[t[0]]], cfg):
+                    runs.append((index[t[0]], cfg))
+    operands = {}
+    for i, pinned in runs:
+        l, d = layers[i], descs[i]
+        if i not in operands:
+            operands.clear()                 # one layer's tensors at a time
+            x, w = W.make_inputs(l)
+            if layout & 1:
+                x = x.transpose(0, 2, 3, 1).copy()
+            P, Q = B.conv_out_shape(d)
+            operands[i] = (torch.from_numpy(x).to(dev), torch.from_numpy(w).to(dev),
+                           torch.empty(l["n"] * l["k"] * P * Q, device=dev, dtype=torch.float32), x.size, w.size)
+            plan.set_weights(i, operands[i][1])
+        xd, wd, yd, nx, nw = operands[i]
+        if pinned is not None:
+            plan.set_layer_config(i, pinned)
         torch.cuda.synchronize()
         cfg = plan.layer_config(i)
         for rep in range(args.warm + args.reps):
@@ -84,9 +111,9 @@ def main():
             order.append({"layer": l["name"], "counted": rep >= args.warm, "config_id": B.config_id(cfg),
                           "config": cfg.asdict(), "kernel": B.config_kernel_name(cfg),
                           "flops": B.conv_flops(d),
-                          "bytes_read": 4 * (x.size + w.size), "bytes_written": 4 * yd.numel()})
+                          "bytes_read": 4 * (nx + nw), "bytes_written": 4 * yd.numel()})
         torch.cuda.synchronize()
-        del xd, wd, yd
+    operands.clear()
     if args.calibrate_copy:
         src = torch.zeros(64 << 20, device=dev, dtype=torch.float32)
         dst = torch.empty_like(src)

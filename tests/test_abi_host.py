@@ -147,7 +147,8 @@ def test_config_encoding_roundtrip_and_constraint_check():
     assert B.config_legal(tiny, B.make_config(128, 64, 16, 2, 2, split_k=1))
     assert B.config_legal(d, B.make_config(128, 64, 16, 2, 2, persist=2))
     assert not B.config_legal(d, B.ConvConfig(128, 64, 16, 2, 2, 2, 0, 2, 2))   # persistent + split
-    assert B.config_legal(d, B.ConvConfig(128, 64, 16, 2, 2, 1, 1, 2, 2))       # persistent + remap
+    assert B.config_legal(d, B.ConvConfig(128, 64, 16, 2, 2, 1, 1, 2, 2))       # persistent: XCD-contiguous
+    assert not B.config_legal(d, B.ConvConfig(128, 64, 16, 2, 2, 1, 0, 2, 2))   # ... and only so
     assert not B.config_legal(d, B.ConvConfig(128, 64, 16, 2, 2, 1, 1, 0, 4))   # stages not in list
     assert B.config_legal(d, B.make_config(128, 64, 16, 2, 2, split_k=3, reduce=1))
     assert B.config_legal(d, B.make_config(128, 64, 16, 2, 2, persist=2, reduce=1))

@@ -29,7 +29,7 @@ def test_every_tile_variant_tap_major():
 
 def test_tap_major_split_and_persistent_schedules():
     """Slices that start in the middle of a tap's channel range, slice counts that do not divide the
-    step count, persistent schedules with and without XCD-contiguous rounds, both ways of summing."""
+    step count, persistent schedules (XCD-contiguous rounds and runs), both ways of summing."""
     l = W.layer("tm_sched", 3, 64, (21, 18), 96, 3, 1, 1, x_dist="u11", w_dist="u11", seed=178)
     desc = B.make_desc(l)
     x, w = W.make_inputs(l)
@@ -40,8 +40,8 @@ def test_tap_major_split_and_persistent_schedules():
             cfgs.append(B.make_config(bm, bn, bk, wm, wn, split, split % 2, stages=1 + split % 3,
                                       reduce=(split // 2) % 2))
         for persist in (1, 2, 3, 4):
-            for remap in (0, 1):
-                cfgs.append(B.ConvConfig(bm, bn, bk, wm, wn, 1, remap, persist, 1 + persist % 3, persist % 2))
+            for reduce in (0, 1):
+                cfgs.append(B.ConvConfig(bm, bn, bk, wm, wn, 1, 1, persist, 1 + persist % 3, reduce))
     ran = 0
     for c in cfgs:
         if not B.config_legal(desc, c):
