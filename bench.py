@@ -116,9 +116,11 @@ def load_traffic_table(path):
 class Runner:
     """One workload on the device: operands, plan, passes, events, oracle check."""
 
-    def __init__(self, B, W, torch, args, name, layers, descs, layout):
+    def __init__(self, B, W, torch, args, name, layers, descs, layout, auto=False):
         self.B, self.W, self.torch, self.args = B, W, torch, args
         self.name, self.layers, self.descs, self.layout = name, layers, descs, layout
+        self.auto = auto                 # the plan chooses each tensor's layout
+        self.codes = [layout] * len(layers)
         self.dev = torch.device("cuda:0")
         self.stream = torch.cuda.current_stream()
 
@@ -126,8 +128,11 @@ class Runner:
         """Search every distinct layer; returns {shape key: report fields} for the rows."""
         B, W = self.B, self.W
         info = {}
-        for l, d in zip(self.layers, self.descs):
-            key = W.shape_key(l)
+        variants = [(l, d) for l, d in zip(self.layers, self.descs)]
+        if self.auto:                    # every layout code of every layer has to be on record
+            variants = [(l, B.make_desc(l, layout=code)) for l in self.layers for code in (1, 2, 3, 0)]
+        for l, d in variants:
+            key = W.shape_key(l) + (d.layout,) if self.auto else W.shape_key(l)
             if key in info:
                 continue
             hit = B.cache_lookup(d) is not None
@@ -157,7 +162,15 @@ class Runner:
         B, W, torch, np = self.B, self.W, self.torch, __import__("numpy")
         layers, descs, dev = self.layers, self.descs, self.dev
         self.epi, self.use_res = epi, "residual" in epi
-        self.plan = B.Plan(descs, tune=False)
+        if self.auto:
+            # every layer of these workloads has tensors of its own: 2i is read, 2i+1 written, all free
+            n = len(layers)
+            self.plan = B.Plan(descs, tune=False, graph=([2 * i for i in range(n)], [2 * i + 1 for i in range(n)],
+                                                         None, [-1] * (2 * n)))
+            self.codes = [self.plan.layer_layout(i) for i in range(n)]
+            descs = self.descs = [B.make_desc(l, layout=c) for l, c in zip(layers, self.codes)]
+        else:
+            self.plan = B.Plan(descs, tune=False)
         self.flops, act_bytes = [], 0
         for l, d in zip(layers, descs):
             P, Q = B.conv_out_shape(d)
@@ -168,19 +181,21 @@ class Runner:
         if cold:
             copies = max(2, min(-(-600 * 2 ** 20 // act_bytes) + 1, (16 * 2 ** 30) // act_bytes))
         self.copies = copies
-        self.host, shared = [], {}
+        self.host, self.own, shared = [], [], {}
         self.xs, self.ys, self.rs = ([[] for _ in range(copies)] for _ in range(3))
         for i, (l, d) in enumerate(zip(layers, descs)):
-            key = (W.shape_key(l), l["seed"]) if copies > 1 else W.shape_key(l)
+            code = self.codes[i]
+            key = (W.shape_key(l), code & 1) + ((l["seed"],) if copies > 1 else ())
+            self.own.append(key not in shared)     # operands from this layer's own seed?
             if key not in shared:
                 x, w = W.make_inputs(l)
-                xh = np.ascontiguousarray(x.transpose(0, 2, 3, 1)) if self.layout & 1 else x
+                xh = np.ascontiguousarray(x.transpose(0, 2, 3, 1)) if code & 1 else x
                 shared[key] = (xh, w, [torch.from_numpy(xh).to(dev) for _ in range(copies)],
                                torch.from_numpy(w).to(dev))
             xh, w, xd, wd = shared[key]
             self.host.append((xh, w))
             P, Q = B.conv_out_shape(d)
-            yshape = (l["n"], P, Q, l["k"]) if self.layout & 2 else (l["n"], l["k"], P, Q)
+            yshape = (l["n"], P, Q, l["k"]) if code & 2 else (l["n"], l["k"], P, Q)
             for c in range(copies):
                 self.xs[c].append(xd[c])
                 self.ys[c].append(torch.empty(yshape, device=dev, dtype=torch.float32))
@@ -251,14 +266,15 @@ class Runner:
         np = __import__("numpy")
         from oracle import conv as oc
         errs, kinds = [], []
-        xl, yl = ("NHWC" if self.layout & 1 else "NCHW"), ("NHWC" if self.layout & 2 else "NCHW")
-        plain = not self.epi and self.layout == 0
         for i, l in enumerate(self.layers):
+            code = self.codes[i]
+            xl, yl = ("NHWC" if code & 1 else "NCHW"), ("NHWC" if code & 2 else "NCHW")
+            plain = not self.epi and code == 0
             c = (self.args.steps - 1) % self.copies if self.copies > 1 else 0
             y_gpu = self.ys[c][i].cpu().numpy().astype(np.float64)
             sh = oc.shape_from_layer(l)
             xh, w = self.host[i]
-            if plain and i in full:
+            if plain and i in full and self.own[i]:   # (a repeated shape runs on its first layer's operands)
                 y_ref, d_ref = full[i]
                 kinds.append("full")
             elif not plain and self.flops[i] <= 8e9:
@@ -267,7 +283,12 @@ class Runner:
                 y_ref, d_ref = oc.conv2d_fused(sh, xh, w, bias=bias, residual=res, relu="relu" in self.epi,
                                                x_layout=xl, y_layout=yl)
                 kinds.append("full")
-            elif plain:
+            elif not self.epi:
+                if code & 2:                       # sample in [N][K][P][Q] order whatever the device's layout
+                    y_gpu = y_gpu.transpose(0, 3, 1, 2)
+                xs_ = xh.transpose(0, 3, 1, 2) if code & 1 else xh
+                xh = np.ascontiguousarray(xs_)
+                y_gpu = np.ascontiguousarray(y_gpu)
                 total = y_gpu.size
                 pq = y_gpu.shape[2] * y_gpu.shape[3]
                 idx = np.random.default_rng(i).integers(0, total, size=min(samples, total))
@@ -314,9 +335,10 @@ def main():
     ap.add_argument("--workspace-limit", type=int, default=None,
                     help="bytes; wpk_set_workspace_limit before tuning (0: atomics instead of a workspace)")
     ap.add_argument("--refine", type=int, default=None, help="refinement rounds of the tuner")
-    ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc", "x_nhwc", "y_nhwc"],
+    ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc", "x_nhwc", "y_nhwc", "auto"],
                     help="activation layout: channels-last x and y, or one of the two mixed forms "
-                         "(the convolution then also transforms the layout)")
+                         "(the convolution then also transforms the layout); auto: every layout code of "
+                         "every layer is searched and the plan chooses each tensor's layout itself")
     ap.add_argument("--pipeline", type=int, default=1, choices=[1, 2],
                     help="2: run the timed passes as two half-batch chains on two streams "
                          "(wpk_plan_set_pipeline); the per-layer event loop stays unsplit")
@@ -336,7 +358,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     dev_name, cus = B.device_info()
-    layout = {"nchw": B.NCHW, "nhwc": B.NHWC, "x_nhwc": B.X_NHWC, "y_nhwc": B.Y_NHWC}[args.layout]
+    layout = {"nchw": B.NCHW, "nhwc": B.NHWC, "x_nhwc": B.X_NHWC, "y_nhwc": B.Y_NHWC, "auto": B.NCHW}[args.layout]
     epi = set(t for t in args.fused.split(",") if t)
     assert epi <= {"bias", "residual", "relu"}, "--fused takes bias,residual,relu"
 
@@ -354,7 +376,7 @@ def main():
     def prepare(name):
         layers, text = workload_layers(W, name)
         descs = [B.make_desc(l, layout=layout) for l in layers]
-        r = Runner(B, W, torch, args, name, layers, descs, layout)
+        r = Runner(B, W, torch, args, name, layers, descs, layout, auto=args.layout == "auto")
         t0 = time.perf_counter()
         info = {} if args.no_tune else r.tune(opt)
         if args.pipeline == 2 and not args.no_tune:     # the half-batch shapes get their own search
@@ -415,8 +437,10 @@ def main():
                "gbs_algorithmic": round(gbs, 1), "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1),
                "bound": bound, "flops": flops[i], "bytes_algorithmic": abytes,
                "max_norm_err": errs[i], "checked": err_kinds[i]}
-        row.update(tune_info.get(W.shape_key(l), {"found_by": "default (no search)"}))
-        hit = traffic.get((l["name"], row["config_id"])) if layout == 0 and not epi else None
+        row.update(tune_info.get(W.shape_key(l) + ((run.codes[i],) if run.auto else ()),
+                                 {"found_by": "default (no search)"}))
+        row["layout_code"] = run.codes[i]
+        hit = traffic.get((l["name"], row["config_id"])) if run.codes[i] == 0 and not epi else None
         if hit:
             row["traffic_bytes"] = {"fetched": hit[0], "written": hit[1],
                                     "over_algorithmic": round((hit[0] + hit[1]) / abytes, 2)}

@@ -252,6 +252,7 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt, int fo
 /* Cache of search results, keyed by every descriptor field ("computationally identical"
  * operators, Section 3.1) plus the device name.  Text file, one line per entry. */
 int wpk_cache_lookup(const wpk_conv_desc *d, wpk_conv_config *out); /* 1 hit, 0 miss          */
+int wpk_cache_lookup_time(const wpk_conv_desc *d, wpk_conv_config *out, double *us); /* also the stored runtime */
 int wpk_cache_store(const wpk_conv_desc *d, const wpk_conv_config *cfg, double us);
 int wpk_cache_clear(void);
 int wpk_cache_size(void);
@@ -283,6 +284,36 @@ typedef struct wpk_plan wpk_plan;
  * reports it as an all-zero configuration.  `tune` = 0 uses cached/default configs, 1 runs wpk_conv_tune on cache misses.
  * Allocates device memory for packed weights and split-K needs; synchronises the device. */
 int wpk_conv_plan(const wpk_conv_desc *layers, int32_t n_layers, int32_t tune, wpk_plan **out);
+
+/*
+ * A plan that chooses the layout of the tensors between its layers (Section 2.1, data layout
+ * transformation).  The caller names tensors by small integers: layer i reads tensor x_tensor[i],
+ * writes tensor y_tensor[i] and, if residual_tensor is not NULL and residual_tensor[i] >= 0, adds
+ * that tensor in its epilogue (it is then stored like the layer's output).  tensor_layout[t] says
+ * what the caller dictates for tensor t: 0 = [N][C][H][W], 1 = channels-last, -1 = the plan's
+ * choice (typically: the network's input and output fixed, everything between free).  The
+ * `layout` field of the descriptors passed in is ignored.  For every layer and every combination
+ * of layouts its two tensors may take, the plan takes the runtime of the cached searched
+ * configuration, searches it (tune != 0), or times the default configuration (tune == 0, a few
+ * milliseconds per combination); then the layouts that minimise the sum over the layers are
+ * chosen (wpk_choose_layouts) and every layer gets the layout code of its two tensors: a layer
+ * whose tensors differ transforms the layout while it computes, at no extra pass over memory.
+ * wpk_plan_tensor_layout tells the caller how to store, or read, tensor t.  Everything else is
+ * as for wpk_conv_plan.  WPK_E_BAD_ARG for tensor numbers out of range or tied tensors fixed to
+ * different layouts.
+ */
+int wpk_conv_plan_graph(const wpk_conv_desc *layers, int32_t n_layers, const int32_t *x_tensor,
+                        const int32_t *y_tensor, const int32_t *residual_tensor,
+                        const int32_t *tensor_layout, int32_t n_tensors, int32_t tune, wpk_plan **out);
+int wpk_plan_tensor_layout(const wpk_plan *plan, int32_t tensor);   /* 0, 1, or a negative status */
+int wpk_plan_layer_layout(const wpk_plan *plan, int32_t layer);     /* WPK_NCHW .. WPK_NHWC        */
+
+/* The optimiser by itself (host only): cost[(i*2 + lx)*2 + ly] is layer i's cost when it reads a
+ * tensor in layout lx and writes one in layout ly (any unit; combinations that cannot occur are
+ * never looked at); chosen[t] receives 0 or 1 for every tensor, *total (may be NULL) the minimised sum. */
+int wpk_choose_layouts(int32_t n_layers, const int32_t *x_tensor, const int32_t *y_tensor,
+                       const int32_t *residual_tensor, const int32_t *tensor_layout, int32_t n_tensors,
+                       const double *cost, int32_t *chosen, double *total);
 
 /* Copy and re-pack layer `layer`'s weights (device pointer, KCRS) into the plan, on `stream`. */
 int wpk_plan_set_weights(wpk_plan *plan, int32_t layer, const float *w, void *stream);

@@ -122,6 +122,7 @@ def lib():
             "wpk_conv_tune": (I, [P(ConvDesc)]),
             "wpk_conv_tune_ex": (I, [P(ConvDesc), P(TuneOptions), I, P(TuneReport)]),
             "wpk_cache_lookup": (I, [P(ConvDesc), P(ConvConfig)]),
+            "wpk_cache_lookup_time": (I, [P(ConvDesc), P(ConvConfig), P(D)]),
             "wpk_cache_store": (I, [P(ConvDesc), P(ConvConfig), D]),
             "wpk_cache_clear": (I, []),
             "wpk_cache_size": (I, []),
@@ -131,6 +132,11 @@ def lib():
                                   P(TuneOptions), i32p, P(D), i32p, i32p, P(D), i32p,
                                   ctypes.c_int32]),
             "wpk_conv_plan": (I, [P(ConvDesc), ctypes.c_int32, ctypes.c_int32, P(V)]),
+            "wpk_conv_plan_graph": (I, [P(ConvDesc), ctypes.c_int32, i32p, i32p, i32p, i32p, ctypes.c_int32,
+                                        ctypes.c_int32, P(V)]),
+            "wpk_plan_tensor_layout": (I, [V, ctypes.c_int32]),
+            "wpk_plan_layer_layout": (I, [V, ctypes.c_int32]),
+            "wpk_choose_layouts": (I, [ctypes.c_int32, i32p, i32p, i32p, i32p, ctypes.c_int32, P(D), i32p, P(D)]),
             "wpk_plan_set_weights": (I, [V, ctypes.c_int32, V, V]),
             "wpk_plan_run": (I, [V, P(V), P(V), V]),
             "wpk_plan_run_layer": (I, [V, ctypes.c_int32, V, V, V]),
@@ -332,6 +338,27 @@ def cache_lookup(desc):
     return c if hit == 1 else None
 
 
+def cache_lookup_time(desc):
+    """(config, stored runtime in microseconds) or None."""
+    c, us = ConvConfig(), ctypes.c_double()
+    hit = _check(lib().wpk_cache_lookup_time(ctypes.byref(desc), ctypes.byref(c), ctypes.byref(us)),
+                 "wpk_cache_lookup_time")
+    return (c, us.value) if hit == 1 else None
+
+
+def choose_layouts(x_tensor, y_tensor, residual_tensor, tensor_layout, cost):
+    """wpk_choose_layouts: cost is n_layers x 2 x 2 (nested lists); returns (layouts, total)."""
+    n, nt = len(x_tensor), len(tensor_layout)
+    i32 = lambda v: (ctypes.c_int32 * len(v))(*[int(e) for e in v])
+    flat = [float(cost[i][lx][ly]) for i in range(n) for lx in range(2) for ly in range(2)]
+    chosen, total = (ctypes.c_int32 * nt)(), ctypes.c_double()
+    _check(lib().wpk_choose_layouts(n, i32(x_tensor), i32(y_tensor),
+                                    i32(residual_tensor) if residual_tensor is not None else None,
+                                    i32(tensor_layout), nt, (ctypes.c_double * len(flat))(*flat), chosen,
+                                    ctypes.byref(total)), "wpk_choose_layouts")
+    return list(chosen), total.value
+
+
 def cache_store(desc, cfg, us=0.0):
     _check(lib().wpk_cache_store(ctypes.byref(desc), ctypes.byref(cfg), float(us)),
            "wpk_cache_store")
@@ -398,13 +425,27 @@ def conv2d_fwd_fused(desc, x, w, y, bias=None, residual=None, relu=False, cfg=No
 class Plan:
     """Owner of a ``wpk_plan*``."""
 
-    def __init__(self, descs, tune=False):
+    def __init__(self, descs, tune=False, graph=None):
+        """``graph`` = (x_tensor, y_tensor, residual_tensor or None, tensor_layout): wpk_conv_plan_graph."""
         arr = (ConvDesc * len(descs))(*descs)
         h = ctypes.c_void_p()
-        _check(lib().wpk_conv_plan(arr, len(descs), 1 if tune else 0, ctypes.byref(h)),
-               "wpk_conv_plan")
+        if graph is None:
+            _check(lib().wpk_conv_plan(arr, len(descs), 1 if tune else 0, ctypes.byref(h)),
+                   "wpk_conv_plan")
+        else:
+            xt, yt, rt, tl = graph
+            i32 = lambda v: (ctypes.c_int32 * len(v))(*[int(e) for e in v])
+            _check(lib().wpk_conv_plan_graph(arr, len(descs), i32(xt), i32(yt), i32(rt) if rt is not None else None,
+                                             i32(tl), len(tl), 1 if tune else 0, ctypes.byref(h)),
+                   "wpk_conv_plan_graph")
         self.handle = h
         self.n = len(descs)
+
+    def tensor_layout(self, tensor):
+        return _check(lib().wpk_plan_tensor_layout(self.handle, tensor), "wpk_plan_tensor_layout")
+
+    def layer_layout(self, layer):
+        return _check(lib().wpk_plan_layer_layout(self.handle, layer), "wpk_plan_layer_layout")
 
     def set_weights(self, layer, w, stream=None):
         _check(lib().wpk_plan_set_weights(self.handle, layer, _ptr(w), _stream(stream)),

@@ -826,6 +826,7 @@ struct wpk_plan {
     // and the pointers it was made for
     std::vector<const float *> chk_ptrs;
     bool chk_independent = false;
+    std::vector<int32_t> tensor_layout;  // wpk_conv_plan_graph: the layout chosen for every tensor
 };
 
 extern "C" {
@@ -1276,6 +1277,107 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int
 }
 
 int wpk_conv_tune(const wpk_conv_desc *d) { return wpk_conv_tune_ex(d, nullptr, 0, nullptr); }
+
+// Runtime of one layer for the layout choice: the cached search result's, a fresh search's, or the
+// default configuration timed under the tuner's protocol (synthetic operands of its own).
+static int layer_runtime_us(const wpk_conv_desc *d, int32_t tune, double *us)
+{
+    wpk_conv_config cfg;
+    if (wpk_cache_lookup_time(d, &cfg, us) == 1 && *us > 0.0) return WPK_OK;
+    Problem pr;
+    int rc = make_problem(d, &pr);
+    if (rc != WPK_OK) return rc;
+    if (!pr.tiled_ok) {  // direct kernel: no estimate worth taking; a large constant keeps it out of the choice
+        *us = 1e9;
+        return WPK_OK;
+    }
+    if (tune) {
+        wpk_tune_report rep;
+        int id = wpk_conv_tune_ex(d, nullptr, 0, &rep);
+        if (id < 0) return id;
+        *us = rep.best_us;
+        return WPK_OK;
+    }
+    TuneCtx t;
+    t.pr = pr;
+    wpk_tune_default_options(&t.opt);
+    t.opt.reps = 3;
+    t.st = nullptr; t.e0 = t.e1 = nullptr;
+    t.x = t.w = t.wp = t.y = t.yref = t.dref = nullptr;
+    t.err_bits = nullptr; t.ktab = nullptr;
+    t.rejected = 0; t.hip_failed = 0;
+    t.phase = WPK_STAGE_DEFAULT;
+    rc = tune_setup(t);
+    if (rc == WPK_OK) {
+        default_config(pr, g_cus, &cfg);
+        double err = 0;
+        rc = measure_us(t, cfg, us, &err);
+        if (rc == WPK_OK && !(*us > 0.0)) rc = WPK_E_VERIFY;
+    }
+    tune_free(t);
+    return rc;
+}
+
+int wpk_conv_plan_graph(const wpk_conv_desc *layers, int32_t n_layers, const int32_t *x_tensor,
+                        const int32_t *y_tensor, const int32_t *residual_tensor,
+                        const int32_t *tensor_layout, int32_t n_tensors, int32_t tune, wpk_plan **out)
+{
+    if (!layers || !out || !x_tensor || !y_tensor || !tensor_layout) return WPK_E_NULL_PTR;
+    if (n_layers <= 0 || n_tensors <= 0) return WPK_E_BAD_ARG;
+    {
+        std::lock_guard<std::mutex> g(g_mu);
+        int rc = ensure_device();
+        if (rc != WPK_OK) return rc;
+    }
+    // validate the graph before anything is timed (the optimiser checks ranges and ties)
+    std::vector<double> cost((size_t)n_layers * 4, 0.0);
+    std::vector<int32_t> chosen(n_tensors, 0);
+    int rc = wpk_choose_layouts(n_layers, x_tensor, y_tensor, residual_tensor, tensor_layout, n_tensors,
+                                cost.data(), chosen.data(), nullptr);
+    if (rc != WPK_OK) return rc;
+    // cost of every layer under every combination its tensors may take; identical layers share it
+    std::map<std::string, double> timed;
+    for (int i = 0; i < n_layers; ++i)
+        for (int lx = 0; lx < 2; ++lx)
+            for (int ly = 0; ly < 2; ++ly) {
+                const int fx = tensor_layout[x_tensor[i]], fy = tensor_layout[y_tensor[i]];
+                if ((fx >= 0 && fx != lx) || (fy >= 0 && fy != ly)) continue;
+                wpk_conv_desc d = layers[i];
+                d.layout = lx | (ly << 1);
+                const std::string key = desc_key(&d);
+                auto it = timed.find(key);
+                if (it == timed.end()) {
+                    double us = 0.0;
+                    rc = layer_runtime_us(&d, tune, &us);
+                    if (rc != WPK_OK) return rc;
+                    it = timed.emplace(key, us).first;
+                }
+                cost[(size_t)i * 4 + lx * 2 + ly] = it->second;
+            }
+    rc = wpk_choose_layouts(n_layers, x_tensor, y_tensor, residual_tensor, tensor_layout, n_tensors, cost.data(),
+                            chosen.data(), nullptr);
+    if (rc != WPK_OK) return rc;
+    std::vector<wpk_conv_desc> laid(layers, layers + n_layers);
+    for (int i = 0; i < n_layers; ++i) laid[i].layout = chosen[x_tensor[i]] | (chosen[y_tensor[i]] << 1);
+    rc = wpk_conv_plan(laid.data(), n_layers, tune, out);
+    if (rc != WPK_OK) return rc;
+    (*out)->tensor_layout = chosen;
+    return WPK_OK;
+}
+
+int wpk_plan_tensor_layout(const wpk_plan *plan, int32_t tensor)
+{
+    if (!plan) return WPK_E_NULL_PTR;
+    if (tensor < 0 || tensor >= (int)plan->tensor_layout.size()) return WPK_E_BAD_ARG;
+    return plan->tensor_layout[tensor];
+}
+
+int wpk_plan_layer_layout(const wpk_plan *plan, int32_t layer)
+{
+    if (!plan) return WPK_E_NULL_PTR;
+    if (layer < 0 || layer >= (int)plan->layers.size()) return WPK_E_BAD_ARG;
+    return plan->layers[layer].pr.d.layout;
+}
 
 int wpk_conv_plan(const wpk_conv_desc *layers, int32_t n_layers, int32_t tune, wpk_plan **out)
 {

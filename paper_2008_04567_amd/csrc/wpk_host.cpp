@@ -533,6 +533,19 @@ int wpk_cache_lookup(const wpk_conv_desc *d, wpk_conv_config *out)
     return 1;
 }
 
+int wpk_cache_lookup_time(const wpk_conv_desc *d, wpk_conv_config *out, double *us)
+{
+    Problem pr;
+    int rc = make_problem(d, &pr);
+    if (rc != WPK_OK) return rc;
+    std::lock_guard<std::mutex> g(g_cache_mu);
+    auto it = g_cache.find(cache_key(d));
+    if (it == g_cache.end()) return 0;
+    if (out) *out = it->second.cfg;
+    if (us) *us = it->second.us;
+    return 1;
+}
+
 int wpk_cache_store(const wpk_conv_desc *d, const wpk_conv_config *cfg, double us)
 {
     if (!cfg) return WPK_E_NULL_PTR;
@@ -598,6 +611,107 @@ int wpk_cache_load(const char *path)
     }
     fclose(f);
     return count;
+}
+
+// ---- layouts of the tensors between layers (Section 2.1, data layout transformation) ----------------
+// Every tensor is stored [N][C][H][W] (0) or channels-last (1); a layer's cost depends on the layouts
+// of the tensor it reads and of the tensor it writes; a residual is read in the layout its layer
+// writes, so the two tensors are tied into one group.  Minimise the sum of the layers' costs over
+// the free groups.  Exact, by elimination along the layer order: a table over the assignments of
+// the groups that layers already seen AND layers still to come refer to (a network's frontier: two
+// to four groups for chains with shortcut branches); a group is minimised out after its last layer,
+// with the minimising value kept per remaining assignment for the way back.
+int wpk_choose_layouts(int32_t n_layers, const int32_t *x_tensor, const int32_t *y_tensor,
+                       const int32_t *residual_tensor, const int32_t *tensor_layout, int32_t n_tensors,
+                       const double *cost, int32_t *chosen, double *total)
+{
+    if (!x_tensor || !y_tensor || !tensor_layout || !cost || !chosen) return WPK_E_NULL_PTR;
+    if (n_layers <= 0 || n_tensors <= 0) return WPK_E_BAD_ARG;
+    for (int i = 0; i < n_layers; ++i)
+        if (x_tensor[i] < 0 || x_tensor[i] >= n_tensors || y_tensor[i] < 0 || y_tensor[i] >= n_tensors ||
+            (residual_tensor && residual_tensor[i] >= n_tensors))
+            return WPK_E_BAD_ARG;
+    for (int t = 0; t < n_tensors; ++t)
+        if (tensor_layout[t] < -1 || tensor_layout[t] > 1) return WPK_E_BAD_ARG;
+    // groups of tied tensors (union-find); a group is fixed if any member is
+    std::vector<int> parent(n_tensors);
+    std::iota(parent.begin(), parent.end(), 0);
+    auto find = [&](int t) { while (parent[t] != t) t = parent[t] = parent[parent[t]]; return t; };
+    if (residual_tensor)
+        for (int i = 0; i < n_layers; ++i)
+            if (residual_tensor[i] >= 0) parent[find(residual_tensor[i])] = find(y_tensor[i]);
+    std::vector<int> fixed(n_tensors, -1), last_use(n_tensors, -1), value(n_tensors, 0);
+    for (int t = 0; t < n_tensors; ++t)
+        if (tensor_layout[t] >= 0) {
+            int r = find(t);
+            if (fixed[r] >= 0 && fixed[r] != tensor_layout[t]) return WPK_E_BAD_ARG;  // tied tensors fixed differently
+            fixed[r] = tensor_layout[t];
+        }
+    for (int i = 0; i < n_layers; ++i) last_use[find(x_tensor[i])] = last_use[find(y_tensor[i])] = i;
+    for (int t = 0; t < n_tensors; ++t)
+        if (find(t) == t && fixed[t] >= 0) value[t] = fixed[t];  // also for groups no layer refers to
+
+    const double kNever = 1e300;
+    const size_t kMaxOpen = 20;
+    struct Closed {
+        int group;
+        std::vector<int> open_after;   // the groups still open once this one is gone, in table order
+        int pos;                       // where it sat among the open groups
+        std::vector<char> best;        // per assignment of open_after: the value that minimised
+    };
+    std::vector<Closed> history;
+    std::vector<int> open;
+    std::vector<double> tab(1, 0.0);
+    auto pos_of = [&](int g) { return (int)(std::find(open.begin(), open.end(), g) - open.begin()); };
+    for (int i = 0; i < n_layers; ++i) {
+        const int gs[2] = {find(x_tensor[i]), find(y_tensor[i])};
+        for (int k = 0; k < 2; ++k) {
+            if (pos_of(gs[k]) < (int)open.size()) continue;
+            if (open.size() >= kMaxOpen) return WPK_E_UNSUPPORTED;  // a frontier no network here comes near
+            const size_t n = tab.size();
+            tab.resize(2 * n);
+            for (size_t st = 0; st < n; ++st) {
+                const double base = tab[st];
+                tab[st] = fixed[gs[k]] == 1 ? kNever : base;
+                tab[st + n] = fixed[gs[k]] == 0 ? kNever : base;
+            }
+            open.push_back(gs[k]);
+        }
+        const int px = pos_of(gs[0]), py = pos_of(gs[1]);
+        for (size_t st = 0; st < tab.size(); ++st)
+            if (tab[st] < kNever) tab[st] += cost[(size_t)i * 4 + ((st >> px) & 1) * 2 + ((st >> py) & 1)];
+        for (int k = 0; k < 2; ++k) {
+            const int g = gs[k];
+            const int p = pos_of(g);
+            if (p == (int)open.size() || last_use[g] != i) continue;  // closed already (x == y group), or used later
+            Closed c;
+            c.group = g;
+            c.pos = p;
+            const size_t n = tab.size() / 2;
+            std::vector<double> next(n);
+            c.best.resize(n);
+            const size_t low = ((size_t)1 << p) - 1;
+            for (size_t r = 0; r < n; ++r) {
+                const size_t s0 = (r & low) | ((r & ~low) << 1), s1 = s0 | ((size_t)1 << p);
+                c.best[r] = tab[s1] < tab[s0] ? 1 : 0;
+                next[r] = std::min(tab[s0], tab[s1]);
+            }
+            open.erase(open.begin() + p);
+            c.open_after = open;
+            tab.swap(next);
+            history.push_back(std::move(c));
+        }
+    }
+    if (tab.size() != 1 || !(tab[0] < kNever)) return WPK_E_BAD_ARG;
+    for (size_t h = history.size(); h-- > 0;) {
+        const Closed &c = history[h];
+        size_t r = 0;
+        for (size_t k = 0; k < c.open_after.size(); ++k) r |= (size_t)value[c.open_after[k]] << k;
+        value[c.group] = c.best[r];
+    }
+    for (int t = 0; t < n_tensors; ++t) chosen[t] = value[find(t)];
+    if (total) *total = tab[0];
+    return WPK_OK;
 }
 
 // ---- tuning options and the engine ---------------------------------------------------------------

@@ -191,3 +191,71 @@ def test_pipelined_pass_on_reused_buffers_of_different_sizes():
         PT.assert_close(got, r, d, "two chains, separate buffers, layer %d" % i)
         a = got.copy()
     plan.destroy()
+
+
+def _run_graph_plan(layers, x_t, y_t, r_t, fixed, tune=False):
+    """Build a plan that chooses its tensors' layouts, run the chain, return (plan facts, outputs in
+    [N][K][P][Q] order) -- and hold every layer to the oracle on the device's own input tensor."""
+    torch, dev = PT.torch_dev()
+    descs = [B.make_desc(l) for l in layers]
+    plan = B.Plan(descs, tune=tune, graph=(x_t, y_t, r_t, fixed))
+    nt = len(fixed)
+    lay = [plan.tensor_layout(t) for t in range(nt)]
+    for i in range(len(layers)):
+        assert plan.layer_layout(i) == lay[x_t[i]] | (lay[y_t[i]] << 1)
+    assert all(f < 0 or f == v for f, v in zip(fixed, lay))
+    x0, _ = W.make_inputs(layers[0])
+    ws = [W.make_inputs(l)[1] for l in layers]
+    for i, w in enumerate(ws):
+        plan.set_weights(i, PT.to_dev(w))
+        plan.set_epilogue(i, None, relu=True)
+    # tensor t as the device holds it (in its chosen layout) and as [N][C][H][W] on the host
+    shape = {x_t[0]: x0.shape}
+    for i, l in enumerate(layers):
+        P, Q = B.conv_out_shape(descs[i])
+        shape[y_t[i]] = (l["n"], l["k"], P, Q)
+    to_layout = lambda a, cl: np.ascontiguousarray(a.transpose(0, 2, 3, 1)) if cl else a
+    dev_t = {t: torch.full((int(np.prod(s)),), 777.0, device=dev) for t, s in shape.items()}
+    dev_t[x_t[0]].copy_(torch.from_numpy(to_layout(x0, lay[x_t[0]]).reshape(-1)))
+    xs = [dev_t[x_t[i]] for i in range(len(layers))]
+    ys = [dev_t[y_t[i]] for i in range(len(layers))]
+    rs = [dev_t[r_t[i]] if r_t is not None and r_t[i] >= 0 else None for i in range(len(layers))]
+    xa, ya = plan.pointer_arrays(xs, ys)
+    plan.run_fused(xa, plan.residual_array(rs), ya)
+    torch.cuda.synchronize()
+    host = {t: dev_t[t].cpu().numpy() for t in dev_t}     # flat, in the chosen layouts
+    names = ("NCHW", "NHWC")
+    for i, l in enumerate(layers):
+        n, k, P, Q = shape[y_t[i]]
+        res = host[r_t[i]] if r_t is not None and r_t[i] >= 0 else None
+        y_ref, d_ref = oc.conv2d_fused(oc.shape_from_layer(l), host[x_t[i]], ws[i], residual=res, relu=True,
+                                       x_layout=names[lay[x_t[i]]], y_layout=names[lay[y_t[i]]])
+        PT.assert_close(host[y_t[i]], y_ref, d_ref, "graph plan layer %d (layout code %d)" % (i, plan.layer_layout(i)))
+    plan.destroy()
+    return lay
+
+
+def test_plan_chooses_the_layouts_of_inner_tensors():
+    """wpk_conv_plan_graph on a three-layer chain whose ends are fixed [N][C][H][W].  (a) With stored
+    runtimes that make the channels-last forms cheaper, both inner tensors move to channels-last: the
+    first layer transforms on its way out, the last on its way in, and every layer still equals the
+    oracle in the layouts chosen.  (b) A residual that ties the first inner tensor to the fixed
+    output keeps that tensor [N][C][H][W].  (c) Without stored runtimes the plan times the defaults
+    itself; whatever it picks must be consistent and correct."""
+    layers = [W.layer("lg.a", 2, 32, (14, 12), 32, 3, 1, 1, x_dist="u11", seed=321),
+              W.layer("lg.b", 2, 32, (14, 12), 32, 1, 1, 0, x_dist="u11", seed=322),
+              W.layer("lg.c", 2, 32, (14, 12), 32, 3, 1, 1, x_dist="u11", seed=323)]
+    x_t, y_t, fixed = [0, 1, 2], [1, 2, 3], [0, -1, -1, 0]
+    B.device_info()                    # cache keys carry the device's name: look at the device first
+    B.cache_clear()
+    for l in layers:                   # stored runtimes: every channels-last side takes 3 us off
+        for code in range(4):
+            d = B.make_desc(l, layout=code)
+            B.cache_store(d, B.config_default(d), us=20.0 - 3.0 * bin(code).count("1"))
+    assert _run_graph_plan(layers, x_t, y_t, None, fixed) == [0, 1, 1, 0]
+    assert _run_graph_plan(layers, x_t, y_t, [-1, -1, 1], fixed) == [0, 0, 1, 0]
+    B.cache_clear()
+    lay = _run_graph_plan(layers, x_t, y_t, None, fixed)
+    print("layouts chosen from timed defaults:", lay, flush=True)
+    assert B.cache_size() == 0         # timing the defaults stores nothing
+    B.cache_clear()
