@@ -99,15 +99,16 @@ def cpu_baseline(W, layers, max_seconds=25.0):
 
 
 def load_traffic_table(path):
-    """Rows of the tracked counter summary: layer, config id, bytes fetched and written per launch
-    (rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled as the file's header says).  {} when absent."""
+    """Rows of the tracked counter summary: bytes fetched and written per launch (rocprofv3 FETCH_SIZE /
+    WRITE_SIZE, scaled as the file's header says) by (layer, bm, bn, split, xcd remap, persist, reduce):
+    K-step, wave grid and prefetch depth do not change the traffic.  {} when absent."""
     table = {}
     try:
         with open(path) as f:
             for line in f:
                 t = line.split()
-                if len(t) >= 4 and not line.startswith("#"):
-                    table[(t[0], int(t[1]))] = (float(t[2]), float(t[3]))
+                if len(t) >= 9 and not line.startswith("#"):
+                    table[(t[0],) + tuple(int(v) for v in t[1:7])] = (float(t[7]), float(t[8]))
     except (OSError, ValueError):
         pass
     return table
@@ -239,12 +240,17 @@ class Runner:
         torch = self.torch
         for s_ in range(warmup):
             self.one_pass(s_)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
+        e0.record(self.stream)       # (the launch stream: the region as the device saw it)
         for s_ in range(steps):
             self.one_pass(s_)
+        e1.record(self.stream)
         torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / steps
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        self.region_ms = e0.elapsed_time(e1) / steps
+        return ms
 
     def per_layer_events(self, steps):
         """`steps` passes layer by layer with an event after every layer on the launch stream."""
@@ -373,13 +379,19 @@ def main():
     if args.refine is not None:
         opt.refine = args.refine
 
+    def two_chains(layers):
+        """Whether the workload is also timed as two half-batch chains: a batch to split, and a pass
+        long enough to repay the fork and join."""
+        return layers[0]["n"] >= 2 and len(layers) >= 16
+
     def prepare(name):
         layers, text = workload_layers(W, name)
         descs = [B.make_desc(l, layout=layout) for l in layers]
         r = Runner(B, W, torch, args, name, layers, descs, layout, auto=args.layout == "auto")
         t0 = time.perf_counter()
         info = {} if args.no_tune else r.tune(opt)
-        if args.pipeline == 2 and not args.no_tune:     # the half-batch shapes get their own search
+        if (args.pipeline == 2 or (name != args.workload and two_chains(layers))) and not args.no_tune:
+            # the half-batch shapes get their own search
             for l in layers:
                 for nh in {(l["n"] + 1) // 2, l["n"] // 2}:
                     dh = B.make_desc(dict(l, n=nh), layout=layout)
@@ -440,7 +452,8 @@ def main():
         row.update(tune_info.get(W.shape_key(l) + ((run.codes[i],) if run.auto else ()),
                                  {"found_by": "default (no search)"}))
         row["layout_code"] = run.codes[i]
-        hit = traffic.get((l["name"], row["config_id"])) if run.codes[i] == 0 and not epi else None
+        hit = traffic.get((l["name"], cfg.bm, cfg.bn, cfg.split_k, cfg.xcd_remap, cfg.persist, cfg.reduce)) \
+            if run.codes[i] == 0 and not epi else None
         if hit:
             row["traffic_bytes"] = {"fetched": hit[0], "written": hit[1],
                                     "over_algorithmic": round((hit[0] + hit[1]) / abytes, 2)}
@@ -450,22 +463,41 @@ def main():
             % (l["name"], row["kernel"], cfg.split_k, cfg.persist, per_layer_us[i], tf,
                row["pct_fp32_mfma_peak"], gbs, row["pct_hbm_peak"], bound,
                "%.2g" % errs[i] if errs[i] is not None else "-", err_kinds[i], row["found_by"]))
-    dom = int(np.argmax(per_layer_us))
-    tb = rows[dom].get("traffic_bytes")
-    traffic_dom = tb["fetched"] + tb["written"] if tb else None
-    if rows[dom]["bound"] == "mfma":
-        roofline = {"bound": "mfma", "achieved": rows[dom]["tflops"], "peak": FP32_MFMA_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(rows[dom]["tflops"] / FP32_MFMA_PEAK_TFLOPS, 4),
-                    "traffic": traffic_dom, "flops_per_launch": flops[dom]}
+    # The dominant kernel is the tiled family itself: every launch of a pass is one of its members.
+    # Its average launch duration over the timed region comes from two events on the launch stream
+    # around that region (launches back to back, as rocprofv3 sees them in the same passes); the
+    # per-layer rows above come from a later loop with an event pair around every launch, which
+    # puts a gap between launches and reads 2-5 us longer per launch.
+    region_us = run.region_ms * 1e3
+    total_bytes = float(sum(r["bytes_algorithmic"] for r in rows))
+    mfma_bound = total_flops / (FP32_MFMA_PEAK_TFLOPS * 1e12) >= total_bytes / (HBM_PEAK_GBS * 1e9)
+    tbs = [r.get("traffic_bytes") for r in rows]
+    traffic_avg = sum(t["fetched"] + t["written"] for t in tbs) / n if all(tbs) else None
+    if mfma_bound:
+        ach = total_flops / (region_us * 1e-6) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": traffic_avg,
+                    "flops_per_launch": total_flops / n}
     else:
-        roofline = {"bound": "hbm", "achieved": rows[dom]["gbs_algorithmic"], "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(rows[dom]["gbs_algorithmic"] / HBM_PEAK_GBS, 4),
-                    "traffic": traffic_dom, "bytes_per_launch": rows[dom]["bytes_algorithmic"]}
-    roofline.update({"kernel": rows[dom]["kernel"], "layer": rows[dom]["layer"],
-                     "avg_us": round(per_layer_us[dom], 2),
-                     "traffic_unit": "bytes per launch, fetched + written, from profiles/%s"
-                                     % os.path.basename(TRAFFIC_TABLE) if traffic_dom else
-                                     "null: no counter run on record for this layer under this configuration"})
+        ach = total_bytes / (region_us * 1e-6) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic_avg,
+                    "bytes_per_launch": total_bytes / n}
+    dom = int(np.argmin([r["tflops"] / FP32_MFMA_PEAK_TFLOPS if r["bound"] == "mfma"
+                         else r["gbs_algorithmic"] / HBM_PEAK_GBS for r in rows]))
+    roofline.update({"kernel": "wpk::igemm_kernel<...> (tiled implicit-GEMM family; all %d launches of a pass: %s)"
+                               % (n, ", ".join(sorted(set(r["kernel"] for r in rows)))),
+                     "launches_per_pass": n, "avg_us": round(region_us / n, 2),
+                     "how": "algorithmic work of a pass / duration of the %d timed passes between two events on the "
+                            "launch stream; avg_us = that duration / launches" % args.steps,
+                     "traffic_unit": "bytes per launch (mean over the pass), fetched + written, from profiles/%s"
+                                     % os.path.basename(TRAFFIC_TABLE) if traffic_avg else
+                                     "null: no counter run on record for some layer under its configuration",
+                     "slowest_layer": {"layer": rows[dom]["layer"], "kernel": rows[dom]["kernel"],
+                                       "us_event_separated": rows[dom]["us"],
+                                       "frac": round(rows[dom]["tflops"] / FP32_MFMA_PEAK_TFLOPS
+                                                     if rows[dom]["bound"] == "mfma"
+                                                     else rows[dom]["gbs_algorithmic"] / HBM_PEAK_GBS, 4)}})
     checked = [e for e in errs if e is not None]
     worst = max(checked) if checked else None
 
@@ -497,6 +529,14 @@ def main():
         r.settle(min(args.settle_ms, 60.0))
         k = max(args.steps, 20)
         ms = r.timed(k, max(args.warmup, 3))
+        ms2 = None
+        if two_chains(r.layers):
+            # the same pass as two half-batch chains on two streams (a schedule of the plan's: the
+            # images of a batch do not depend on each other); repays its fork and join on long stacks
+            r.plan.set_pipeline(2)
+            ms2 = r.timed(k, max(args.warmup, 3))
+            r.plan.set_pipeline(1)
+            r.timed(1, 0)  # (the outputs that are checked below come from the plain schedule)
         per = [float(np.mean(v)) for v in r.per_layer_events(min(k, 20))]
         e, kinds = r.check({}, 2048)
         ce = [v for v in e if v is not None]
@@ -515,6 +555,8 @@ def main():
                         "slowest_per_flop": {"layer": r.layers[slow]["name"], "us": round(per[slow], 2),
                                              "tflops": round(r.flops[slow] / per[slow] / 1e6, 2)},
                         "layer_us": {l["name"]: round(p, 2) for l, p in zip(r.layers, per)}}
+        if ms2 is not None:
+            stacks[name]["ms_per_pass_two_half_batch_chains"] = round(ms2, 5)
         log("stack %-14s %3d layers  %.4f ms per pass  %6.2f TFLOP/s  max err %s  (%.1f s)"
             % (name, len(r.layers), ms, tfl, "%.2g" % max(ce) if ce else "-", time.perf_counter() - t0))
         r.plan.destroy()

@@ -142,6 +142,21 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     __shared__ __attribute__((aligned(16))) float lds[2 * (XTILE + WTILE)];
     float *const Xs0 = lds, *const Ws0 = lds + 2 * XTILE;
 
+    // The arguments span several 64-byte lines that no cache holds when a launch begins, and the
+    // set-up below reads them in dependent batches (work iterator, then descriptors, then
+    // divisors): one memory round trip per batch.  Touching every line first puts all of them in
+    // flight at once; the loads below then hit the scalar cache.
+    {
+        static_assert(sizeof(IgemmArgs) <= 320, "one more line to touch");
+        const unsigned long long kp = (unsigned long long)__builtin_amdgcn_kernarg_segment_ptr();
+        int l0, l1, l2, l3, l4, l5;  // (the sixth line holds the launch dimensions the compiler appends)
+        asm volatile("s_load_dword %0, %6, 0x0\n\ts_load_dword %1, %6, 0x40\n\ts_load_dword %2, %6, 0x80\n\t"
+                     "s_load_dword %3, %6, 0xc0\n\ts_load_dword %4, %6, 0x100\n\ts_load_dword %5, %6, 0x140\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&s"(l0), "=&s"(l1), "=&s"(l2), "=&s"(l3), "=&s"(l4), "=&s"(l5)
+                     : "s"(kp)
+                     : "memory");
+    }
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
