@@ -108,9 +108,11 @@ typedef struct wpk_conv_config {
     int32_t xcd_remap; /* 0: tiles in launch order; 1: contiguous tile ranges per XCD (persistent:   */
                        /* within each whole round of tiles)                                        */
     int32_t persist;   /* 0: one workgroup per tile and slice; 1..4: that many persistent          */
-                       /* workgroups per compute unit, the reduction steps of the tiles that do   */
-                       /* not fill a whole round dealt out evenly among them and done first       */
-                       /* (split_k must be 1)                                                      */
+                       /* workgroups per compute unit taking whole tiles round by round; the      */
+                       /* reduction steps of the tiles that do not fill a whole round are dealt   */
+                       /* out evenly in runs, to further workgroups of the same launch when the   */
+                       /* device holds them all at once, else to the first workgroups, which do   */
+                       /* their run before their tiles (split_k must be 1)                        */
     int32_t stages;    /* input tiles in flight in registers between global memory and LDS: 1..3   */
     int32_t reduce;    /* how workgroups that share a tile (split_k > 1 or persist > 0) add up:      */
                        /* 0: partial tiles through a device workspace, the last to arrive sums and */

@@ -513,6 +513,7 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
         a.sk_groups = (int32_t)groups;
         a.sk_q = groups > 0 ? (int32_t)(units / groups) : 0;
         a.sk_rem = groups > 0 ? (int32_t)(units % groups) : 0;
+        a.runners = 0;  // (the launcher decides: it knows how many workgroups of the variant a compute unit holds)
     }
     a.div_pq = make_fastdiv((uint32_t)a.PQ);
     a.div_q = make_fastdiv((uint32_t)a.Q);
@@ -1154,7 +1155,7 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int
             const int cus = g_cus > 0 ? g_cus : 256;
             for (const auto &sh : kShapes) {
                 wpk_conv_config c = {sh[0], sh[1], sh[2], sh[3], sh[4], 1, 0, 0, sh[5], 0};
-                for (int p = 2; p <= 4; ++p) {
+                for (int p = 1; p <= 4; ++p) {
                     c.persist = p;
                     c.xcd_remap = 1;
                     c.reduce = 0;

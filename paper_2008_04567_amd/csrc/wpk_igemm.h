@@ -147,7 +147,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     // divisors): one memory round trip per batch.  Touching every line first puts all of them in
     // flight at once; the loads below then hit the scalar cache.
     {
-        static_assert(sizeof(IgemmArgs) <= 320, "one more line to touch");
+        static_assert(sizeof(IgemmArgs) <= 328, "one more line to touch");
         const unsigned long long kp = (unsigned long long)__builtin_amdgcn_kernarg_segment_ptr();
         int l0, l1, l2, l3, l4, l5;  // (the sixth line holds the launch dimensions the compiler appends)
         asm volatile("s_load_dword %0, %6, 0x0\n\ts_load_dword %1, %6, 0x40\n\ts_load_dword %2, %6, 0x80\n\t"
@@ -711,26 +711,35 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     // persist  > 0: gridDim.x = G persistent workgroups.  Each takes whole tiles g, g+G, ...
     //   of the first tiles_dp = floor(tiles/G)*G tiles.  The reduction steps of the remaining
     //   tiles, laid end to end (`units` of them), are cut into runs of q or q+1 steps (the first
-    //   `rem` get q+1), one for each of the first sk_groups workgroups: all G of them, unless
-    //   that would make the runs too short to be worth a prologue; a workgroup does its run first,
-    //   then its whole tiles.  A run that does
+    //   `rem` get q+1), sk_groups of them: G, unless that would make the runs too short to be
+    //   worth a prologue.  Either sk_groups further workgroups are appended to the grid and take
+    //   one run each (a.runners: whenever all of them fit the device beside the G), or each of
+    //   the first sk_groups workgroups does a run first, then its whole tiles.  A run that does
     //   not cover a tile's whole reduction shares the tile with its neighbours in g: fix-up
     //   through the workspace if the host gave one, else atomics into zeroed y.
     // (tiles_dp, sk_groups, q = sk_q, rem = sk_rem and the divisors come from the host: they
     // depend on the launch alone, and all of it fits 32 bits)
     const bool persistent = a.persist > 0;
-    const int G = gridDim.x, g = blockIdx.x;
+    const int g = blockIdx.x;
+    // With a.runners > 0 the grid is grid_persist + runners workgroups: the first grid_persist take
+    // whole tiles only, the others one dealt-out run each and nothing else, so that a run and a
+    // whole tile of the same compute unit proceed side by side instead of one after the other.
+    const int G = a.runners ? a.grid_persist : (int)gridDim.x;
+    const bool runner = a.runners && g >= G;
     int next_dp = g;
     // (remap: run number gr instead of g, so that consecutive runs -- neighbouring tiles, the
-    // slices of one tile -- sit on one XCD and share its L2)
-    const int gr = a.remap ? xcd_remap(g, G) : g;
+    // slices of one tile -- sit on one XCD and share its L2; G is a multiple of the number of XCDs,
+    // so a runner's XCD is (g - G) % 8 as well)
+    const int gl = runner ? g - G : g;
+    const int gr = a.remap ? xcd_remap(gl, runner ? a.runners : G) : gl;
     int u0, u1;
     {
         const cold_ptr c = cold_args();
         const int q = c->sk_q, rem = c->sk_rem;
-        const bool dealt = persistent && gr < c->sk_groups;
+        const bool dealt = persistent && gr < c->sk_groups && (!a.runners || runner);
         u0 = dealt ? gr * q + min(gr, rem) : 0;
         u1 = dealt ? (gr + 1) * q + min(gr + 1, rem) : 0;
+        if (runner) next_dp = c->tiles_dp;  // no whole tiles
     }
     bool once = !persistent;
     for (;;) {
@@ -782,17 +791,36 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     }
 }
 
+template <int BM, int BN, int BK, int WM, int WN, int PD, int XL>
+hipError_t launch_gather_form(IgemmArgs a, hipStream_t stream)
+{
+    const auto kernel = igemm_kernel<BM, BN, BK, WM, WN, PD, XL>;
+    if (a.persist > 0 && a.tiles_dp > 0 && a.sk_groups > 0) {
+        // The tiles beyond the whole rounds go to workgroups of their own when every workgroup of
+        // the larger grid is resident at once (how many a compute unit holds is asked once per
+        // kernel); otherwise the first sk_groups workgroups do a run before their tiles.  (With no
+        // whole round there is nothing to run beside: the grid stays as it is.)
+        static int resident = -1;  // workgroups per compute unit; benign race: every writer stores the same value
+        if (resident < 0) {
+            int n = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, 64 * WM * WN, 0) != hipSuccess) n = 0;
+            (void)hipGetLastError();
+            resident = n;
+        }
+        const long long cus = a.grid_persist / a.persist;
+        if ((long long)resident * cus >= (long long)a.grid_persist + a.sk_groups) a.runners = a.sk_groups;
+    }
+    dim3 grid((unsigned)(a.persist > 0 ? a.grid_persist + a.runners : a.tiles_m * a.tiles_n * a.split_k));
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * WM * WN), 0, stream, a);
+    return hipGetLastError();
+}
+
 template <int BM, int BN, int BK, int WM, int WN, int PD>
 hipError_t launch_igemm(const IgemmArgs &a, hipStream_t stream)
 {
-    dim3 grid((unsigned)(a.persist > 0 ? a.grid_persist : a.tiles_m * a.tiles_n * a.split_k));
-    if (a.xl == 2)
-        hipLaunchKernelGGL((igemm_kernel<BM, BN, BK, WM, WN, PD, 1>), grid, dim3(64 * WM * WN), 0, stream, a);
-    else if (a.xl == 3)
-        hipLaunchKernelGGL((igemm_kernel<BM, BN, BK, WM, WN, PD, 2>), grid, dim3(64 * WM * WN), 0, stream, a);
-    else
-        hipLaunchKernelGGL((igemm_kernel<BM, BN, BK, WM, WN, PD, 0>), grid, dim3(64 * WM * WN), 0, stream, a);
-    return hipGetLastError();
+    if (a.xl == 2) return launch_gather_form<BM, BN, BK, WM, WN, PD, 1>(a, stream);
+    if (a.xl == 3) return launch_gather_form<BM, BN, BK, WM, WN, PD, 2>(a, stream);
+    return launch_gather_form<BM, BN, BK, WM, WN, PD, 0>(a, stream);
 }
 
 }  // namespace wpk

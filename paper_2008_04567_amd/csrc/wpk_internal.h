@@ -124,6 +124,9 @@ struct IgemmArgs {
     int32_t tiles_m, tiles_n, remap;
     int32_t persist;       // 0, or persistent workgroups per compute unit
     int32_t grid_persist;  // persist * compute units
+    int32_t runners;       // persistent: workgroups appended to the grid that do a dealt-out run and nothing else
+                           // (set by the launcher: sk_groups, or 0 when the first sk_groups workgroups do their run
+                           // themselves)
     uint32_t x_bytes;   // size of x
     uint32_t x_bias;    // (pad_h*W + pad_w)*4: added to every tap offset, subtracted from the base
     uint32_t w_bytes;   // size of the packed weights

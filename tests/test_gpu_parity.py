@@ -70,6 +70,31 @@ def test_persistent_schedule():
                     PT.assert_close(y, y_ref, d_ref, repr(c) + " launch %d" % again)
 
 
+def test_persistent_runs_beside_and_before_whole_tiles():
+    """More tiles than one round of persistent workgroups, with a remainder: the remainder's
+    reduction steps are dealt out in runs.  Small tiles leave room on a compute unit, so the runs
+    go to workgroups appended to the grid and proceed beside the whole tiles; four workgroups of
+    four waves per compute unit leave no room (and the largest tile may not either), so there the
+    first workgroups do a run before their tiles.  Both gather forms
+    ([N][C][H][W] with C = 8: row by row; C = 32: one filter tap per step), both ways of summing."""
+    for c_in, seed in ((8, 91), (32, 92)):
+        l = W.layer("rounds_and_rest_c%d" % c_in, 19, c_in, (64, 64), 128, 3, 1, 1, x_dist="u11", w_dist="u11", seed=seed)
+        desc = B.make_desc(l)
+        x, w = W.make_inputs(l)
+        y_ref, d_ref = PT.oracle_full(l, x, w)
+        cfgs = [B.make_config(256, 128, 16, 4, 2, persist=1, stages=1),                 # 304 tiles on 256 workgroups
+                B.make_config(256, 128, 16, 4, 2, persist=1, stages=1, reduce=1)]
+        for persist in (1, 2, 3, 4):                                                    # 2432 tiles
+            cfgs.append(B.make_config(64, 64, 16, 2, 2, persist=persist, xcd_remap=1, stages=2, reduce=persist % 2))
+        cfgs.append(B.make_config(64, 32, 16, 2, 1, persist=3, xcd_remap=1))            # 4864 tiles on 768 + runners
+        for c in cfgs:
+            assert B.config_legal(desc, c), c
+            print(l["name"], c, flush=True)
+            for again in range(2):
+                y = PT.run_gpu(l, x, w, cfg=c)
+                PT.assert_close(y, y_ref, d_ref, repr(c) + " launch %d" % again)
+
+
 def test_split_k_and_remap_settings():
     desc = B.make_desc(RAGGED)
     x, w = W.make_inputs(RAGGED)
