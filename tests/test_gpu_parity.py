@@ -367,7 +367,7 @@ def test_illegal_config_is_refused_before_launch():
 
 @pytest.mark.parametrize("layer", W.config3() + W.config4(), ids=lambda l: l["name"])
 def test_full_size_configs_3_and_4(layer):
-    """Full BASELINE sizes (N=16), whole output tensor against the oracle."""
+    """The full sizes of the batched 3x3 workload (N=16), whole output tensor against the oracle."""
     print(layer["name"], B.config_default(B.make_desc(layer)), flush=True)
     PT.check_layer(layer)
 
