@@ -518,6 +518,9 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     a.div_pq = make_fastdiv((uint32_t)a.PQ);
     a.div_q = make_fastdiv((uint32_t)a.Q);
     a.div_tiles_n = make_fastdiv((uint32_t)a.tiles_n);
+    a.div_tiles_m = make_fastdiv((uint32_t)a.tiles_m);
+    // weights the larger operand: tiles that share them are made neighbours (see IgemmArgs::mfast)
+    a.mfast = pr.w_elems > pr.x_elems ? 1 : 0;
     a.div_tiles = make_fastdiv((uint32_t)a.tiles);
     a.div_nsteps = make_fastdiv((uint32_t)a.nsteps);
     a.div_q1 = make_fastdiv((uint32_t)a.sk_q + 1);
@@ -546,7 +549,8 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
         int tiles = a.tiles_m * a.tiles_n;
         int tiles_dp = tiles / a.grid_persist * a.grid_persist;
         if (tiles_dp < tiles) {
-            int m_begin = tiles_dp / a.tiles_n * cfg.bm;
+            // (tiles ordered along the pixels first: the remainder is a range of channels, not of pixels)
+            int m_begin = a.mfast ? 0 : tiles_dp / a.tiles_n * cfg.bm;
             if (m_begin == 0) {
                 int rc = y_zeroed ? WPK_OK : zero_fill(y, pr.y_elems, st);
                 if (rc != WPK_OK) return rc;

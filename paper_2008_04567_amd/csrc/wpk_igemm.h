@@ -147,7 +147,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     // divisors): one memory round trip per batch.  Touching every line first puts all of them in
     // flight at once; the loads below then hit the scalar cache.
     {
-        static_assert(sizeof(IgemmArgs) <= 328, "one more line to touch");
+        static_assert(sizeof(IgemmArgs) + 32 <= 6 * 64, "one more line to touch");
         const unsigned long long kp = (unsigned long long)__builtin_amdgcn_kernarg_segment_ptr();
         int l0, l1, l2, l3, l4, l5;  // (the sixth line holds the launch dimensions the compiler appends)
         asm volatile("s_load_dword %0, %6, 0x0\n\ts_load_dword %1, %6, 0x40\n\ts_load_dword %2, %6, 0x80\n\t"
@@ -191,8 +191,13 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     int tile_m, tile_n;
     {
         const cold_ptr c = cold_args();
-        tile_m = fdiv(tile, WPK_COLD_DIV(c, div_tiles_n));
-        tile_n = tile - tile_m * c->tiles_n;
+        if (c->mfast) {
+            tile_n = fdiv(tile, WPK_COLD_DIV(c, div_tiles_m));
+            tile_m = tile - tile_n * c->tiles_m;
+        } else {
+            tile_m = fdiv(tile, WPK_COLD_DIV(c, div_tiles_n));
+            tile_n = tile - tile_m * c->tiles_n;
+        }
     }
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 

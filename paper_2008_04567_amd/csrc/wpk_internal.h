@@ -148,6 +148,10 @@ struct IgemmArgs {
                         // tiles, nsteps, sk_q + 1, max(sk_q, 1)
     FastDiv div_tap;    // by what a reduction row index is divided to find its first table entry: C where a
                         // K-step lies inside one filter tap, else R*S
+    int32_t mfast;      // order of the tiles: 0: tile = tile_m * tiles_n + tile_n (neighbours in the order share rows
+                        // of x); 1: tile = tile_n * tiles_m + tile_m (neighbours share weights) -- whichever operand is
+                        // the larger, since with XCD-contiguous ranges the other one is what every XCD fetches whole
+    FastDiv div_tiles_m;  // by tiles_m
     int32_t xl;         // 0: x is [N][C][H][W]; 1: channels-last, gathered row by row; 2: channels-last,
                         // gathered as 16-byte channel quads (reduction rows ordered (r, s, c)); 3: [N][C][H][W]
                         // with the reduction ordered (r, s, c), one filter tap per step
