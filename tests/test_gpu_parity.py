@@ -95,6 +95,32 @@ def test_persistent_runs_beside_and_before_whole_tiles():
                 PT.assert_close(y, y_ref, d_ref, repr(c) + " launch %d" % again)
 
 
+def test_tiles_numbered_along_the_pixels_first():
+    """Weights larger than the activations: the tiles are numbered along the pixels first (neighbours in
+    the order share weights).  Plain, split and persistent schedules -- 288 tiles on 256 persistent
+    workgroups, so a whole round plus a remainder that is a range of channels --, both ways of summing
+    (with atomics the whole output is zeroed first), plain and with the fused epilogue."""
+    l = W.layer("heavy_w", 2, 256, (24, 24), 512, 3, 1, 1, x_dist="u11", w_dist="u11", seed=93)
+    desc = B.make_desc(l)
+    x, w = W.make_inputs(l)
+    assert w.size > x.size
+    y_ref, d_ref = PT.oracle_full(l, x, w)
+    bias, res = _fused_operands(l, 16)
+    f_ref, fd_ref = oc.conv2d_fused(oc.shape_from_layer(l), x, w, bias=bias, residual=res, relu=True)
+    cfgs = [B.make_config(64, 32, 16, 2, 1), B.make_config(64, 32, 16, 2, 1, 5, 1), B.make_config(64, 32, 16, 2, 1, 3, 0, reduce=1)]
+    for persist in (1, 2):
+        for reduce in (0, 1):
+            cfgs.append(B.make_config(64, 32, 16, 2, 1, persist=persist, reduce=reduce))
+    cfgs.append(B.make_config(128, 64, 32, 4, 2, persist=1))
+    for c in cfgs:
+        assert B.config_legal(desc, c), c
+        print(l["name"], c, flush=True)
+        for again in range(2):
+            PT.assert_close(PT.run_gpu(l, x, w, cfg=c), y_ref, d_ref, repr(c) + " launch %d" % again)
+        PT.assert_close(PT.run_gpu_fused(l, x, w, bias=bias, residual=res, relu=True, cfg=c), f_ref, fd_ref,
+                        repr(c) + " fused")
+
+
 def test_split_k_and_remap_settings():
     desc = B.make_desc(RAGGED)
     x, w = W.make_inputs(RAGGED)
