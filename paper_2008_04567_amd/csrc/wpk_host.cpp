@@ -257,6 +257,20 @@ void default_config(const Problem &pr, int compute_units, wpk_conv_config *out)
             return;
         }
     }
+    // Between one and two tiles per compute unit: one persistent workgroup per compute unit takes a
+    // whole tile, the steps of the other tiles are dealt out in runs that proceed beside them (a
+    // split reduction would share every tile instead of the remainder only).
+    if (tiles > compute_units && tiles < 2 * (int64_t)compute_units && nsteps >= 8) {
+        wpk_conv_config h = c;
+        h.split_k = 1;
+        h.xcd_remap = 1;
+        h.persist = 1;
+        h.reduce = 0;
+        if (legal_for(pr, h)) {
+            *out = h;
+            return;
+        }
+    }
     // atomics where many slices meet in a small output (zeroing it is cheap and the last
     // workgroup need not read every slot); the workspace otherwise
     int64_t per = (nsteps + c.split_k - 1) / c.split_k, slices = (nsteps + per - 1) / per;

@@ -805,15 +805,18 @@ hipError_t launch_gather_form(IgemmArgs a, hipStream_t stream)
         // the larger grid is resident at once (how many a compute unit holds is asked once per
         // kernel); otherwise the first sk_groups workgroups do a run before their tiles.  (With no
         // whole round there is nothing to run beside: the grid stays as it is.)
-        static int resident = -1;  // workgroups per compute unit; benign race: every writer stores the same value
-        if (resident < 0) {
-            int n = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, 64 * WM * WN, 0) != hipSuccess) n = 0;
-            (void)hipGetLastError();
-            resident = n;
+        static std::atomic<int> resident{-1};  // workgroups per compute unit (every writer stores the same value)
+        int n = resident.load(std::memory_order_relaxed);
+        if (n < 0) {
+            n = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, 64 * WM * WN, 0) != hipSuccess) {
+                (void)hipGetLastError();
+                n = 0;
+            }
+            resident.store(n, std::memory_order_relaxed);
         }
         const long long cus = a.grid_persist / a.persist;
-        if ((long long)resident * cus >= (long long)a.grid_persist + a.sk_groups) a.runners = a.sk_groups;
+        if ((long long)n * cus >= (long long)a.grid_persist + a.sk_groups) a.runners = a.sk_groups;
     }
     dim3 grid((unsigned)(a.persist > 0 ? a.grid_persist + a.runners : a.tiles_m * a.tiles_n * a.split_k));
     hipLaunchKernelGGL(kernel, grid, dim3(64 * WM * WN), 0, stream, a);

@@ -175,6 +175,18 @@ def test_default_config_is_legal_for_every_workload_layer():
         assert B.config_legal(d, B.config_default(d)), l["name"]
 
 
+def test_default_config_schedules_by_tile_count():
+    """The untuned rule: just over whole rounds of three workgroups per compute unit (784 tiles on 256
+    compute units) -> three persistent workgroups; between one and two tiles per compute unit (392) ->
+    one; fewer tiles than compute units -> the reduction split (host rule, no device needed: 256
+    compute units assumed)."""
+    c64, c128, c256, c512 = (B.config_default(B.make_desc(l)) for l in W.config3())
+    assert (c64.persist, c64.split_k, c64.xcd_remap) == (3, 1, 1)
+    assert (c128.persist, c128.split_k, c128.xcd_remap, c128.reduce) == (1, 1, 1, 0)
+    assert c256.persist == 0 and c256.split_k > 1
+    assert c512.persist == 0 and c512.split_k > 1
+
+
 def test_cache_roundtrip_and_identity_criterion(tmp_path):
     B.cache_clear()
     a, b = W.config3()[0], W.config3()[1]
