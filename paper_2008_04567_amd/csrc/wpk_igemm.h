@@ -149,7 +149,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     {
         static_assert(sizeof(IgemmArgs) + 32 <= 6 * 64, "one more line to touch");
         const unsigned long long kp = (unsigned long long)__builtin_amdgcn_kernarg_segment_ptr();
-        int l0, l1, l2, l3, l4, l5;  // (the sixth line holds the launch dimensions the compiler appends)
+        int l0, l1, l2, l3, l4, l5;  // (the sixth line also holds the launch dimensions the compiler appends)
         asm volatile("s_load_dword %0, %6, 0x0\n\ts_load_dword %1, %6, 0x40\n\ts_load_dword %2, %6, 0x80\n\t"
                      "s_load_dword %3, %6, 0xc0\n\ts_load_dword %4, %6, 0x100\n\ts_load_dword %5, %6, 0x140\n\t"
                      "s_waitcnt lgkmcnt(0)"
