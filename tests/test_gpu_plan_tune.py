@@ -268,6 +268,40 @@ def test_plan_run_can_be_captured_in_a_hip_graph(ways):
     plan.destroy()
 
 
+def test_first_launch_of_a_persistent_kernel_may_be_inside_a_capture():
+    """A persistent launch with whole rounds asks the runtime, once per kernel, how many workgroups a
+    compute unit holds.  That first launch may be the one a caller captures: the capture must go
+    through and the replays must give the oracle's result.  (A tile shape no other test in this
+    process is likely to have launched with whole rounds: 128x32 with four waves along the pixels.)"""
+    from oracle import conv as oc
+    torch, dev = PT.torch_dev()
+    l = W.layer("cap", 12, 8, (48, 64), 32, 3, 1, 1, x_dist="u11", seed=84)     # 288 tiles of 128x32
+    cfg = B.make_config(128, 32, 8, 4, 1, persist=1, stages=3)
+    desc = B.make_desc(l)
+    assert B.config_legal(desc, cfg)
+    plan = B.Plan([desc])
+    plan.set_layer_config(0, cfg)
+    x, w = W.make_inputs(l)
+    plan.set_weights(0, PT.to_dev(w))
+    xd = PT.to_dev(x)
+    y = torch.full((12, 32, 48, 64), float("nan"), device=dev)
+    xa, ya = plan.pointer_arrays([xd], [y])
+    r, d, _ = oc.conv2d(oc.shape_from_layer(l), x, w)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            plan.run(xa, ya, s)
+        for rep in range(2):
+            y.fill_(float("nan"))
+            g.replay()
+            torch.cuda.synchronize()
+            PT.assert_close(y.cpu().numpy(), r, d, "replay %d" % rep)
+    del g
+    plan.destroy()
+
+
 def test_measured_peaks_are_plausible_and_skippable():
     """The calibration entry point: an MFMA-only kernel cannot exceed the published fp32 matrix peak
     (256 CUs x 256 FLOP per clock x 2.4 GHz) by more than clock tolerance, and a copy stays under the
