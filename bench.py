@@ -373,7 +373,8 @@ def main():
     if args.cache and os.path.exists(args.cache):
         log("loaded %d cached search results" % B.cache_load(args.cache))
     # the timed region runs whole passes of a plan on separate buffers: outputs that a layer sums
-    # into with atomics are zeroed once per pass, so candidates are timed without that launch
+    # into with atomics are zeroed once per pass, so on long passes candidates are timed without
+    # that launch (prepare() decides per workload)
     opt = B.tune_default_options(mode=args.tune_mode, verbose=1 if args.verbose_tune else 0,
                                  zero_ahead=0 if args.pipeline == 2 else 1, epilogue=1 if epi else 0)
     if args.refine is not None:
@@ -389,6 +390,9 @@ def main():
         descs = [B.make_desc(l, layout=layout) for l in layers]
         r = Runner(B, W, torch, args, name, layers, descs, layout, auto=args.layout == "auto")
         t0 = time.perf_counter()
+        # (a short pass cannot spread the one zeroing launch over many layers: there a candidate that
+        # sums with atomics is timed with a zeroing launch of its own)
+        opt.zero_ahead = 1 if args.pipeline != 2 and len(layers) > 8 else 0
         info = {} if args.no_tune else r.tune(opt)
         if (args.pipeline == 2 or (name != args.workload and two_chains(layers))) and not args.no_tune:
             # the half-batch shapes get their own search
