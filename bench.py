@@ -380,6 +380,9 @@ def main():
     if args.refine is not None:
         opt.refine = args.refine
 
+    def layers_of(name):
+        return workload_layers(W, name)[0]
+
     def two_chains(layers):
         """Whether the workload is also timed as two half-batch chains: a batch to split, and a pass
         long enough to repay the fork and join."""
@@ -566,9 +569,35 @@ def main():
         r.plan.destroy()
         del r
         torch.cuda.empty_cache()
+        if two_chains(layers_of(name)) and layout == 0 and not args.no_tune and not epi:
+            # the same stack with the plan choosing every tensor's layout (Section 2.1's layout
+            # transformation): each layer is searched under the four combinations of layouts its two
+            # tensors can take, the plan picks the combination per layer, a layer whose tensors
+            # differ transforms while it computes
+            t1 = time.perf_counter()
+            ls, _ = workload_layers(W, name)
+            ra = Runner(B, W, torch, args, name, ls, [B.make_desc(l) for l in ls], 0, auto=True)
+            ra.tune(opt)
+            ra.setup(epi, False)
+            ra.settle(min(args.settle_ms, 60.0))
+            ms_a = ra.timed(k, max(args.warmup, 3))
+            ea, _ = ra.check({}, 2048)
+            cea = [v for v in ea if v is not None]
+            stacks[name]["chosen_layouts"] = {
+                "ms_per_pass": round(ms_a, 5), "max_norm_err": max(cea) if cea else None,
+                "layers_by_layout_code": {str(c): ra.codes.count(c) for c in sorted(set(ra.codes))},
+                "layout_codes": "bit 0: x channels-last, bit 1: y channels-last",
+                "search_seconds": round(time.perf_counter() - t1, 1)}
+            log("stack %-14s with chosen layouts %.4f ms per pass, layers by layout code %s  (%.1f s)"
+                % (name, ms_a, stacks[name]["chosen_layouts"]["layers_by_layout_code"], time.perf_counter() - t1))
+            ra.plan.destroy()
+            del ra
+            torch.cuda.empty_cache()
     if stacks:
         out["stacks"] = stacks
         errs_all = [v["max_norm_err"] for v in stacks.values() if v["max_norm_err"] is not None]
+        errs_all += [v["chosen_layouts"]["max_norm_err"] for v in stacks.values()
+                     if "chosen_layouts" in v and v["chosen_layouts"]["max_norm_err"] is not None]
         if worst is not None and errs_all:
             out["max_norm_err_all_workloads"] = max([worst] + errs_all)
 
@@ -595,7 +624,9 @@ def main():
     if cpu_rec is not None:
         out["cpu_baseline"] = cpu_rec
     print(json.dumps(out), flush=True)
-    bad = [v for v in [worst] + [s["max_norm_err"] for s in stacks.values()] if v is not None and not v <= TOL]
+    bad = [v for v in [worst] + [s["max_norm_err"] for s in stacks.values()]
+           + [s["chosen_layouts"]["max_norm_err"] for s in stacks.values() if "chosen_layouts" in s]
+           if v is not None and not v <= TOL]
     if bad:
         log("FAILED: an output differs from the oracle by more than %g of its normaliser" % TOL)
         sys.exit(1)
