@@ -96,14 +96,23 @@ int wpk_last_hip_error(void);
  * the library was built with, its LDS and workgroup size must fit a gfx950 compute unit,
  * split_k may not exceed the number of reduction steps, and the persistent schedule excludes
  * split_k > 1 and always has xcd_remap = 1.
+ *
+ * Two forms of kernel share the genes.  With bm >= 64 a workgroup stages a bm x bn tile's operands
+ * through LDS and its wm x wn waves each own a part of the tile (the tiled members).  With bm = 32
+ * (the wave-split members, for launches of a few microseconds: single images, layers of few
+ * pixels) a workgroup owns a 32 x bn tile and its wm * wn waves cut the reduction between them,
+ * each fetching its operands straight into registers, and add their partial tiles up in LDS;
+ * these take bk = 8 (they work in octets of reduction rows), need the reduction ordered
+ * (r, s, c) (C a multiple of 32) and have no persistent schedule.
  */
 #define WPK_N_GENES 10
 typedef struct wpk_conv_config {
-    int32_t bm;        /* output pixels per workgroup tile:      64, 128, 256                        */
+    int32_t bm;        /* output pixels per workgroup tile:      32 (wave-split), 64, 128, 256      */
     int32_t bn;        /* output channels per workgroup tile:    32, 64, 128                        */
     int32_t bk;        /* reduction (c,r,s) entries per step:    8, 16, 32                          */
     int32_t wm;        /* waves along the pixel dimension:       1, 2, 4                            */
     int32_t wn;        /* waves along the channel dimension:     1, 2, 4                            */
+                       /* (bm = 32: wm * wn = 1, 2, 4 or 8 waves along the reduction)               */
     int32_t split_k;   /* slices of the reduction done by separate workgroups: 1 .. 16, 20, 24     */
     int32_t xcd_remap; /* 0: tiles in launch order; 1: contiguous tile ranges per XCD (persistent:   */
                        /* within each whole round of tiles)                                        */
@@ -114,6 +123,7 @@ typedef struct wpk_conv_config {
                        /* device holds them all at once, else to the first workgroups, which do   */
                        /* their run before their tiles (split_k must be 1)                        */
     int32_t stages;    /* input tiles in flight in registers between global memory and LDS: 1..3   */
+                       /* (bm = 32: four octets in flight per wave for each)                        */
     int32_t reduce;    /* how workgroups that share a tile (split_k > 1 or persist > 0) add up:      */
                        /* 0: partial tiles through a device workspace, the last to arrive sums and */
                        /*    stores (no zeroing of y, fused epilogue applied in the same launch);   */

@@ -64,7 +64,7 @@ def build_library(force=True, verbose=False):
     hipcc = _hipcc()
     src = lambda f: os.path.join(CSRC, f)
     headers = [os.path.join(INCLUDE, "wpk.h"), src("wpk_internal.h")]
-    kernel_headers = headers + [src("wpk_igemm.h"), src("wpk_variants.def")]
+    kernel_headers = headers + [src("wpk_igemm.h"), src("wpk_wsplit.h"), src("wpk_variants.def")]
     jobs, objs = [], []
 
     def add(cmd, deps):

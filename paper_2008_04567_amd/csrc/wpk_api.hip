@@ -1184,6 +1184,27 @@ int wpk_conv_tune_ex(const wpk_conv_desc *d, const wpk_tune_options *opt_in, int
                     }
                 }
             }
+            // small launches: the wave-split members, two or four waves per tile, the reduction cut
+            // between workgroups to about one wave per SIMD (half and twice that as well)
+            if (wave_split_candidate(pr, 65536)) {
+                const int64_t blocks = ((pr.M + 31) / 32) * ((pr.d.k + 31) / 32), octets = pr.CRS / 8;
+                for (int wk = 2; wk <= 4; wk += 2)
+                    for (int st = 1; st <= 2; ++st) {
+                        wpk_conv_config c = {kWaveSplitBm, 32, 8, wk, 1, 1, 1, 0, st, 0};
+                        const int64_t want = std::max<int64_t>(1, 4 * (int64_t)cus / (blocks * wk));
+                        for (int i = 0; i < kGeneCounts[5]; ++i) {
+                            const int sk = kSplitVals[i];
+                            if (2 * sk < want || sk > 2 * want || (sk > 1 && octets / (wk * sk) < 4)) continue;
+                            c.split_k = sk;
+                            c.reduce = 0;
+                            consider(c);
+                            if (sk > 1) {
+                                c.reduce = 1;
+                                consider(c);
+                            }
+                        }
+                    }
+            }
         }
         // one gene of the winner at a time, every other value of it
         t.phase = WPK_STAGE_REFINE;

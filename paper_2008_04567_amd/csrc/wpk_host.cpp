@@ -16,7 +16,7 @@
 
 namespace wpk {
 
-const int32_t kBmVals[3] = {64, 128, 256};
+const int32_t kBmVals[4] = {32, 64, 128, 256};
 const int32_t kBnVals[3] = {32, 64, 128};
 const int32_t kBkVals[3] = {8, 16, 32};
 const int32_t kWmVals[3] = {1, 2, 4};
@@ -26,7 +26,7 @@ const int32_t kRemapVals[2] = {0, 1};
 const int32_t kPersistVals[5] = {0, 1, 2, 3, 4};
 const int32_t kStageVals[3] = {1, 2, 3};
 const int32_t kReduceVals[2] = {0, 1};
-const int kGeneCounts[WPK_N_GENES] = {3, 3, 3, 3, 3, 18, 2, 5, 3, 2};
+const int kGeneCounts[WPK_N_GENES] = {4, 3, 3, 3, 3, 18, 2, 5, 3, 2};
 
 const int32_t *gene_values(int g)
 {
@@ -166,8 +166,14 @@ bool legal_for(const Problem &pr, const wpk_conv_config &cfg)
     if (find_variant(cfg.bm, cfg.bn, cfg.bk, cfg.wm, cfg.wn, cfg.stages) < 0) return false;
     int threads = 64 * cfg.wm * cfg.wn;
     if (threads > 1024) return false;                                             // workgroup size
-    if (2 * (cfg.bk + 4) * (cfg.bm + cfg.bn) * 4 > kMaxLdsBytes) return false;    // two LDS stages
-    if (threads > cfg.bm && (cfg.bk * cfg.bm / threads) % 4 != 0) return false;   // whole k quads per thread
+    if (cfg.bm == kWaveSplitBm) {
+        // the wave-split members: tap-major reduction order only, one workgroup per tile and slice
+        if (!(pr.tapmajor || pr.xquad) || cfg.persist != 0) return false;
+        if ((cfg.wm * cfg.wn - 1) * cfg.bn * 32 * 4 > kMaxLdsBytes) return false;  // the other waves' partial tiles
+    } else {
+        if (2 * (cfg.bk + 4) * (cfg.bm + cfg.bn) * 4 > kMaxLdsBytes) return false;    // two LDS stages
+        if (threads > cfg.bm && (cfg.bk * cfg.bm / threads) % 4 != 0) return false;   // whole k quads per thread
+    }
     int32_t nsteps = (pr.CRS + cfg.bk - 1) / cfg.bk;
     if (cfg.split_k > nsteps) return false;
     // the persistent schedule balances the reduction itself: no fixed slices; and it always maps
@@ -230,9 +236,36 @@ FixupNeed fixup_need(const Problem &pr, const wpk_conv_config &cfg, int compute_
 // atomics rather than through the workspace.  Falls back to a crude cost model over all
 // variants if that choice is illegal for the shape.
 static void model_config(const Problem &pr, int compute_units, wpk_conv_config *out);
+bool wave_split_candidate(const Problem &pr, int64_t max_block_octets)
+{
+    if (!(pr.tapmajor || pr.xquad)) return false;
+    const int64_t blocks = ((pr.M + 31) / 32) * ((pr.d.k + 31) / 32), octets = pr.CRS / 8;
+    return blocks * octets <= max_block_octets;
+}
+static bool wave_split_default(const Problem &pr, int compute_units, wpk_conv_config *out)
+{
+    if (!wave_split_candidate(pr, 20000)) return false;
+    const int64_t blocks = ((pr.M + 31) / 32) * ((pr.d.k + 31) / 32), octets = pr.CRS / 8;
+    const int wk = 4;
+    int64_t want = std::max<int64_t>(1, 4 * (int64_t)compute_units / (blocks * wk));
+    while (want > 1 && octets / (wk * want) < 12) --want;
+    wpk_conv_config c = {kWaveSplitBm, 32, 8, wk, 1, 1, 1, 0, 1, 0};
+    for (int i = 0; i < kGeneCounts[5]; ++i)
+        if (kSplitVals[i] <= want) c.split_k = kSplitVals[i];
+    c.reduce = c.split_k >= 8 ? 1 : 0;
+    if (!legal_for(pr, c)) return false;
+    *out = c;
+    return true;
+}
 void default_config(const Problem &pr, int compute_units, wpk_conv_config *out)
 {
     if (compute_units <= 0) compute_units = 256;
+    // A launch with a few microseconds of arithmetic at most (single images, late layers): the
+    // wave-split members, four waves per 32 x 32 tile, the reduction cut further between workgroups
+    // until about one wave per SIMD is busy, but not into runs of fewer than twelve octets; many
+    // slices add up with atomics.  (Measured on the single-image ResNet-50 layers: 4.3-9.8 us where
+    // the tiled members' best is 4.9-10.6.)
+    if (wave_split_default(pr, compute_units, out)) return;
     wpk_conv_config c = {64, pr.d.k <= 32 ? 32 : 64, pr.CRS >= 64 ? 32 : pr.CRS >= 32 ? 16 : 8, 2,
                          pr.d.k <= 32 ? 1 : 2, 1, 1, 0, 2, 0};
     int64_t tiles = ((pr.M + c.bm - 1) / c.bm) * ((pr.d.k + c.bn - 1) / c.bn);
@@ -292,6 +325,7 @@ static void model_config(const Problem &pr, int compute_units, wpk_conv_config *
     wpk_conv_config bc = {128, 64, 16, 2, 2, 1, 1, 0, 2, 0};
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
+        if (v.bm == kWaveSplitBm) continue;  // (the model prices LDS-staged tiles)
         for (int si = 0; si < kGeneCounts[5]; ++si) {
             wpk_conv_config c = {v.bm, v.bn, v.bk, v.wm, v.wn, kSplitVals[si], 1, 0, v.stages, 0};
             if (!legal_for(pr, c)) continue;

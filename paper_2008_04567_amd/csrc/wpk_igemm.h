@@ -67,6 +67,18 @@ __device__ __forceinline__ void static_for(F &&f)
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
+// f(0) && f(1) && ... && f(N-1), left to right, stopping at the first false.
+template <class F, int... I>
+__device__ __forceinline__ bool static_all_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    return (f(std::integral_constant<int, I>{}) && ...);
+}
+template <int N, class F>
+__device__ __forceinline__ bool static_all(F &&f)
+{
+    return static_all_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 __device__ __forceinline__ int fdiv(int n, const FastDiv &f)
 {
     return (int)((__umulhi((unsigned)n, f.mul) + (unsigned)n) >> f.sh);
@@ -94,11 +106,206 @@ __device__ __forceinline__ cold_ptr cold_args()
     return (cold_ptr)p;
 }
 
+// The arguments span several 64-byte lines that no cache holds when a launch begins, and a kernel's
+// set-up reads them in dependent batches (work iterator, then descriptors, then divisors): one
+// memory round trip per batch.  Touching every line first puts all of them in flight at once; the
+// loads after it hit the scalar cache.
+__device__ __forceinline__ void touch_kernarg_lines()
+{
+    static_assert(sizeof(IgemmArgs) + 32 <= 6 * 64, "one more line to touch");
+    const unsigned long long kp = (unsigned long long)__builtin_amdgcn_kernarg_segment_ptr();
+    int l0, l1, l2, l3, l4, l5;  // (the sixth line also holds the launch dimensions the compiler appends)
+    asm volatile("s_load_dword %0, %6, 0x0\n\ts_load_dword %1, %6, 0x40\n\ts_load_dword %2, %6, 0x80\n\t"
+                 "s_load_dword %3, %6, 0xc0\n\ts_load_dword %4, %6, 0x100\n\ts_load_dword %5, %6, 0x140\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&s"(l0), "=&s"(l1), "=&s"(l2), "=&s"(l3), "=&s"(l4), "=&s"(l5)
+                 : "s"(kp)
+                 : "memory");
+}
+
 // The tap table is read through the constant address space: wave-uniform scalar loads.
 typedef const int __attribute__((address_space(4))) *tap_ptr;
 
 // LDS row pitch (floats) of a reduction-contiguous tile with BK k values per column.
 __host__ __device__ constexpr int lds_pitch(int bk) { return bk + 4; }
+
+// Gather state of output pixel m: voff = byte offset of its window origin in x (before padding is
+// subtracted; the padding shift is folded into the tap offsets and the buffer base, so it is never
+// negative); inv: bit r set = filter row r is outside the image for this pixel, bit 16+s = column s;
+// bit 31 is always set and is what the table's padding rows point at.  A pixel past the last one
+// has every bit set.
+__device__ __forceinline__ void pixel_window(const cold_ptr c, const int m, int &voff, unsigned &inv_out)
+{
+    voff = 0;
+    inv_out = 0xffffffffu;
+    if (m < c->M) {
+        int n = fdiv(m, WPK_COLD_DIV(c, div_pq)), pq = m - n * c->PQ;
+        int p = fdiv(pq, WPK_COLD_DIV(c, div_q)), q = pq - p * c->Q;
+        int ih0 = p * c->stride_h - c->pad_h, iw0 = q * c->stride_w - c->pad_w;
+        // channels-last x: c->xl 1 or 2; [N][C][H][W]: 0 or 3
+        voff = (c->xl == 1 || c->xl == 2) ? ((n * c->H + p * c->stride_h) * c->W + q * c->stride_w) * c->C * 4
+                                          : ((n * c->C * c->H + p * c->stride_h) * c->W + q * c->stride_w) * 4;
+        unsigned inv = 0x80000000u;
+        // rows below the image are r < -ih0, rows past it r >= H - ih0 when the dilation is 1:
+        // two clamped shifts instead of a loop over the filter
+        auto outside = [](int o0, int len, int taps) WPK_LAMBDA {
+            const int lo = min(max(-o0, 0), taps), hi = min(max(len - o0, 0), taps);
+            return ((1u << lo) - 1u) | (((1u << taps) - 1u) & ~((1u << hi) - 1u));
+        };
+        if (c->dil_h == 1) {
+            inv |= outside(ih0, c->H, c->R);
+        } else {
+            for (int r = 0; r < c->R; ++r) {
+                int ih = ih0 + r * c->dil_h;
+                if (ih < 0 || ih >= c->H) inv |= 1u << r;
+            }
+        }
+        if (c->dil_w == 1) {
+            inv |= outside(iw0, c->W, c->S) << 16;
+        } else {
+            for (int sx = 0; sx < c->S; ++sx) {
+                int iw = iw0 + sx * c->dil_w;
+                if (iw < 0 || iw >= c->W) inv |= 1u << (16 + sx);
+            }
+        }
+        inv_out = inv;
+    }
+}
+
+// ---- what leaves a wave: its NNT x NMT accumulator blocks, whose first pixel is mbase and first
+//      channel nbase, go to y -- plain stores with the fused epilogue applied, or fp32 atomics ----
+template <int NNT, int NMT>
+__device__ __forceinline__ void store_wave_tile(const cold_ptr ce, const v16f (&acc)[NNT * NMT], const int mbase,
+                                                const int nbase, const int lrow, const int lcol, const bool atomic)
+{
+    // the host applies the epilogue itself after a launch that accumulates with atomics
+    const bool fused = !atomic && (ce->bias || ce->res || ce->relu);
+
+    // ---- epilogue: D[row = channel][col = pixel]; register e of lane l holds row
+    //      8*(e/4) + 4*(l/32) + e%4 and column l%32 of its 32x32 block.  Buffer addressing: one
+    //      32-bit lane offset per block plus a wave-uniform offset per register, instead of a
+    //      64-bit address per output.  A NULL bias or residual becomes a buffer of zero records,
+    //      whose loads return 0. ------------------------------------------------------------------
+    const __amdgpu_buffer_rsrc_t yrsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)ce->y, 0, (int)ce->y_bytes, 0x00020000);
+    // y[n][k][p][q]: consecutive channels are PQ elements apart; channels-last y[n][p][q][k]: 1
+    const int PQ4 = ce->yl ? 4 : ce->PQ * 4;
+    static_for<NMT>([&](auto J) WPK_LAMBDA {
+        constexpr int j = decltype(J)::value;
+        int m = mbase + j * 32 + lcol;
+        if (m < ce->M) {
+            int n = fdiv(m, WPK_COLD_DIV(ce, div_pq)), pq = m - n * ce->PQ;
+            static_for<NNT>([&](auto I) WPK_LAMBDA {
+                constexpr int i = decltype(I)::value;
+                const int kbase = nbase + i * 32 + 4 * lrow;  // + 8*(e/4) + e%4
+                // byte offset of (n, kbase, pq) in y; only used for channels below K, where it
+                // is below y_bytes < 2^32
+                const unsigned voff = ce->yl ? (unsigned)(((size_t)m * ce->K + kbase) * 4)
+                                           : (unsigned)((((size_t)n * ce->K + kbase) * ce->PQ + pq) * 4);
+                // A 32-channel block that lies wholly below K (the usual case) stores without a
+                // bound check per register; the check costs an exec-mask round trip each.
+                auto emit = [&](auto FULL, auto THROUGH) WPK_LAMBDA {
+                    constexpr bool full = decltype(FULL)::value;
+                    // channels-last outputs leave a lane in 16-byte pieces that only the L2 merges
+                    // into whole lines: they keep the default write-back policy
+                    constexpr int policy = decltype(THROUGH)::value ? kYStorePolicy : 0;
+                    if (ce->yl == 2 && !atomic) {
+                        // channels-last y with K a multiple of 4 and 16-byte aligned tensors: the four
+                        // registers 4g..4g+3 of a lane are four consecutive channels of its pixel
+                        const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
+                            (void *)(ce->bias ? ce->bias : ce->y), 0, ce->bias ? ce->K * 4 : 0, 0x00020000);
+                        const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
+                            (void *)(ce->res ? ce->res : ce->y), 0, ce->res ? (int)ce->y_bytes : 0, 0x00020000);
+                        v4f add[4];
+                        if (fused)
+                            static_for<4>([&](auto G) WPK_LAMBDA {
+                                constexpr int g = decltype(G)::value;
+                                v4f t = __builtin_bit_cast(
+                                    v4f, __builtin_amdgcn_raw_buffer_load_b128(brsrc, kbase * 4, 32 * g, 0));
+                                if (full || kbase + 8 * g < ce->K)
+                                    t += __builtin_bit_cast(
+                                        v4f, __builtin_amdgcn_raw_buffer_load_b128(rrsrc, voff, 32 * g, 0));
+                                add[g] = t;
+                            });
+                        static_for<4>([&](auto G) WPK_LAMBDA {
+                            constexpr int g = decltype(G)::value;
+                            if (full || kbase + 8 * g < ce->K) {
+                                v4f v = {acc[i * NMT + j][4 * g], acc[i * NMT + j][4 * g + 1],
+                                         acc[i * NMT + j][4 * g + 2], acc[i * NMT + j][4 * g + 3]};
+                                if (fused) {
+                                    v += add[g];
+                                    if (ce->relu)
+                                        v = (v4f){fmaxf(v[0], 0.0f), fmaxf(v[1], 0.0f), fmaxf(v[2], 0.0f),
+                                                  fmaxf(v[3], 0.0f)};
+                                }
+                                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), yrsrc, voff,
+                                                                       32 * g, policy);
+                            }
+                        });
+                    } else if (fused) {
+                        const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
+                            (void *)(ce->bias ? ce->bias : ce->y), 0, ce->bias ? ce->K * 4 : 0, 0x00020000);
+                        const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
+                            (void *)(ce->res ? ce->res : ce->y), 0, ce->res ? (int)ce->y_bytes : 0, 0x00020000);
+                        // everything the 16 outputs of this block add is fetched first, so the loads
+                        // are all in flight together; then the stores
+                        float add[16];
+                        static_for<16>([&](auto E) WPK_LAMBDA {
+                            constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
+                            float t = __builtin_bit_cast(
+                                float, __builtin_amdgcn_raw_buffer_load_b32(brsrc, kbase * 4, de * 4, 0));
+                            if (full || kbase + de < ce->K)
+                                t += __builtin_bit_cast(
+                                    float, __builtin_amdgcn_raw_buffer_load_b32(rrsrc, voff, de * PQ4, 0));
+                            add[e] = t;
+                        });
+                        static_for<16>([&](auto E) WPK_LAMBDA {
+                            constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
+                            if (full || kbase + de < ce->K) {
+                                float v = acc[i * NMT + j][e] + add[e];
+                                v = ce->relu ? fmaxf(v, 0.0f) : v;
+                                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
+                                                                      voff, de * PQ4, policy);
+                            }
+                        });
+                    } else if (atomic) {
+                        // (no-return fp32 adds, addressed like the stores)
+                        static_for<16>([&](auto E) WPK_LAMBDA {
+                            constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
+                            if (full || kbase + de < ce->K) {
+                                const float v = acc[i * NMT + j][e];
+                                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(v, yrsrc, voff, de * PQ4, 0);
+                            }
+                        });
+                    } else {
+                        static_for<16>([&](auto E) WPK_LAMBDA {
+                            constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
+                            if (full || kbase + de < ce->K) {
+                                // a copy first: a bit cast taken straight from a vector element
+                                // reads element 0 with this compiler
+                                const float v = acc[i * NMT + j][e];
+                                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
+                                                                      voff, de * PQ4, policy);
+                            }
+                        });
+                    }
+                };
+                const bool whole = nbase + i * 32 + 32 <= ce->K;
+                if (ce->yl == 0) {
+                    if (whole)
+                        emit(std::true_type{}, std::true_type{});
+                    else
+                        emit(std::false_type{}, std::true_type{});
+                } else {
+                    if (whole)
+                        emit(std::true_type{}, std::false_type{});
+                    else
+                        emit(std::false_type{}, std::false_type{});
+                }
+            });
+        }
+    });
+}
 
 // XL = 0: reduction rows ordered (c, r, s) and gathered one row at a time as described above, for
 //   activations [N][C][H][W] or (a.xl = 1) channels-last ones: only the window origin and the
@@ -142,21 +349,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     __shared__ __attribute__((aligned(16))) float lds[2 * (XTILE + WTILE)];
     float *const Xs0 = lds, *const Ws0 = lds + 2 * XTILE;
 
-    // The arguments span several 64-byte lines that no cache holds when a launch begins, and the
-    // set-up below reads them in dependent batches (work iterator, then descriptors, then
-    // divisors): one memory round trip per batch.  Touching every line first puts all of them in
-    // flight at once; the loads below then hit the scalar cache.
-    {
-        static_assert(sizeof(IgemmArgs) + 32 <= 6 * 64, "one more line to touch");
-        const unsigned long long kp = (unsigned long long)__builtin_amdgcn_kernarg_segment_ptr();
-        int l0, l1, l2, l3, l4, l5;  // (the sixth line also holds the launch dimensions the compiler appends)
-        asm volatile("s_load_dword %0, %6, 0x0\n\ts_load_dword %1, %6, 0x40\n\ts_load_dword %2, %6, 0x80\n\t"
-                     "s_load_dword %3, %6, 0xc0\n\ts_load_dword %4, %6, 0x100\n\ts_load_dword %5, %6, 0x140\n\t"
-                     "s_waitcnt lgkmcnt(0)"
-                     : "=&s"(l0), "=&s"(l1), "=&s"(l2), "=&s"(l3), "=&s"(l4), "=&s"(l5)
-                     : "s"(kp)
-                     : "memory");
-    }
+    touch_kernarg_lines();
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -212,41 +405,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
     const cold_ptr c = cold_args();
     static_for<XP>([&](auto I) WPK_LAMBDA {
         constexpr int i = decltype(I)::value;
-        int m = m0 + pm0 + i * T;
-        xvoff[i] = 0;
-        xinv[i] = 0xffffffffu;
-        if (m < c->M) {
-            int n = fdiv(m, WPK_COLD_DIV(c, div_pq)), pq = m - n * c->PQ;
-            int p = fdiv(pq, WPK_COLD_DIV(c, div_q)), q = pq - p * c->Q;
-            int ih0 = p * c->stride_h - c->pad_h, iw0 = q * c->stride_w - c->pad_w;
-            // channels-last x: c->xl 1 or 2; [N][C][H][W]: 0 or 3
-            xvoff[i] = (c->xl == 1 || c->xl == 2) ? ((n * c->H + p * c->stride_h) * c->W + q * c->stride_w) * c->C * 4
-                                                : ((n * c->C * c->H + p * c->stride_h) * c->W + q * c->stride_w) * 4;
-            unsigned inv = 0x80000000u;
-            // rows below the image are r < -ih0, rows past it r >= H - ih0 when the dilation is 1:
-            // two clamped shifts instead of a loop over the filter
-            auto outside = [](int o0, int len, int taps) WPK_LAMBDA {
-                const int lo = min(max(-o0, 0), taps), hi = min(max(len - o0, 0), taps);
-                return ((1u << lo) - 1u) | (((1u << taps) - 1u) & ~((1u << hi) - 1u));
-            };
-            if (c->dil_h == 1) {
-                inv |= outside(ih0, c->H, c->R);
-            } else {
-                for (int r = 0; r < c->R; ++r) {
-                    int ih = ih0 + r * c->dil_h;
-                    if (ih < 0 || ih >= c->H) inv |= 1u << r;
-                }
-            }
-            if (c->dil_w == 1) {
-                inv |= outside(iw0, c->W, c->S) << 16;
-            } else {
-                for (int sx = 0; sx < c->S; ++sx) {
-                    int iw = iw0 + sx * c->dil_w;
-                    if (iw < 0 || iw >= c->W) inv |= 1u << (16 + sx);
-                }
-            }
-            xinv[i] = inv;
-        }
+        pixel_window(c, m0 + pm0 + i * T, xvoff[i], xinv[i]);
     });
     };
     const int wvoff = (wkq * a.Kpad + n0 + wkout) * 16;
@@ -580,134 +739,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const IgemmArgs a)
             }
         }
     }
-    const bool atomic = mode == kAtomic;
-    // the host applies the epilogue itself after a launch that accumulates with atomics
-    const bool fused = !atomic && (ce->bias || ce->res || ce->relu);
-
-    // ---- epilogue: D[row = channel][col = pixel]; register e of lane l holds row
-    //      8*(e/4) + 4*(l/32) + e%4 and column l%32 of its 32x32 block.  Buffer addressing: one
-    //      32-bit lane offset per block plus a wave-uniform offset per register, instead of a
-    //      64-bit address per output.  A NULL bias or residual becomes a buffer of zero records,
-    //      whose loads return 0. ------------------------------------------------------------------
-    const __amdgpu_buffer_rsrc_t yrsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void *)ce->y, 0, (int)ce->y_bytes, 0x00020000);
-    // y[n][k][p][q]: consecutive channels are PQ elements apart; channels-last y[n][p][q][k]: 1
-    const int PQ4 = ce->yl ? 4 : ce->PQ * 4;
-    static_for<NMT>([&](auto J) WPK_LAMBDA {
-        constexpr int j = decltype(J)::value;
-        int m = m0 + wave_m * TM + j * 32 + lcol;
-        if (m < ce->M) {
-            int n = fdiv(m, WPK_COLD_DIV(ce, div_pq)), pq = m - n * ce->PQ;
-            static_for<NNT>([&](auto I) WPK_LAMBDA {
-                constexpr int i = decltype(I)::value;
-                const int kbase = n0 + wave_n * TN + i * 32 + 4 * lrow;  // + 8*(e/4) + e%4
-                // byte offset of (n, kbase, pq) in y; only used for channels below K, where it
-                // is below y_bytes < 2^32
-                const unsigned voff = ce->yl ? (unsigned)(((size_t)m * ce->K + kbase) * 4)
-                                           : (unsigned)((((size_t)n * ce->K + kbase) * ce->PQ + pq) * 4);
-                // A 32-channel block that lies wholly below K (the usual case) stores without a
-                // bound check per register; the check costs an exec-mask round trip each.
-                auto emit = [&](auto FULL, auto THROUGH) WPK_LAMBDA {
-                    constexpr bool full = decltype(FULL)::value;
-                    // channels-last outputs leave a lane in 16-byte pieces that only the L2 merges
-                    // into whole lines: they keep the default write-back policy
-                    constexpr int policy = decltype(THROUGH)::value ? kYStorePolicy : 0;
-                    if (ce->yl == 2 && !atomic) {
-                        // channels-last y with K a multiple of 4 and 16-byte aligned tensors: the four
-                        // registers 4g..4g+3 of a lane are four consecutive channels of its pixel
-                        const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
-                            (void *)(ce->bias ? ce->bias : ce->y), 0, ce->bias ? ce->K * 4 : 0, 0x00020000);
-                        const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
-                            (void *)(ce->res ? ce->res : ce->y), 0, ce->res ? (int)ce->y_bytes : 0, 0x00020000);
-                        v4f add[4];
-                        if (fused)
-                            static_for<4>([&](auto G) WPK_LAMBDA {
-                                constexpr int g = decltype(G)::value;
-                                v4f t = __builtin_bit_cast(
-                                    v4f, __builtin_amdgcn_raw_buffer_load_b128(brsrc, kbase * 4, 32 * g, 0));
-                                if (full || kbase + 8 * g < ce->K)
-                                    t += __builtin_bit_cast(
-                                        v4f, __builtin_amdgcn_raw_buffer_load_b128(rrsrc, voff, 32 * g, 0));
-                                add[g] = t;
-                            });
-                        static_for<4>([&](auto G) WPK_LAMBDA {
-                            constexpr int g = decltype(G)::value;
-                            if (full || kbase + 8 * g < ce->K) {
-                                v4f v = {acc[i * NMT + j][4 * g], acc[i * NMT + j][4 * g + 1],
-                                         acc[i * NMT + j][4 * g + 2], acc[i * NMT + j][4 * g + 3]};
-                                if (fused) {
-                                    v += add[g];
-                                    if (ce->relu)
-                                        v = (v4f){fmaxf(v[0], 0.0f), fmaxf(v[1], 0.0f), fmaxf(v[2], 0.0f),
-                                                  fmaxf(v[3], 0.0f)};
-                                }
-                                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), yrsrc, voff,
-                                                                       32 * g, policy);
-                            }
-                        });
-                    } else if (fused) {
-                        const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
-                            (void *)(ce->bias ? ce->bias : ce->y), 0, ce->bias ? ce->K * 4 : 0, 0x00020000);
-                        const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
-                            (void *)(ce->res ? ce->res : ce->y), 0, ce->res ? (int)ce->y_bytes : 0, 0x00020000);
-                        // everything the 16 outputs of this block add is fetched first, so the loads
-                        // are all in flight together; then the stores
-                        float add[16];
-                        static_for<16>([&](auto E) WPK_LAMBDA {
-                            constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
-                            float t = __builtin_bit_cast(
-                                float, __builtin_amdgcn_raw_buffer_load_b32(brsrc, kbase * 4, de * 4, 0));
-                            if (full || kbase + de < ce->K)
-                                t += __builtin_bit_cast(
-                                    float, __builtin_amdgcn_raw_buffer_load_b32(rrsrc, voff, de * PQ4, 0));
-                            add[e] = t;
-                        });
-                        static_for<16>([&](auto E) WPK_LAMBDA {
-                            constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
-                            if (full || kbase + de < ce->K) {
-                                float v = acc[i * NMT + j][e] + add[e];
-                                v = ce->relu ? fmaxf(v, 0.0f) : v;
-                                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
-                                                                      voff, de * PQ4, policy);
-                            }
-                        });
-                    } else if (atomic) {
-                        // (no-return fp32 adds, addressed like the stores)
-                        static_for<16>([&](auto E) WPK_LAMBDA {
-                            constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
-                            if (full || kbase + de < ce->K) {
-                                const float v = acc[i * NMT + j][e];
-                                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(v, yrsrc, voff, de * PQ4, 0);
-                            }
-                        });
-                    } else {
-                        static_for<16>([&](auto E) WPK_LAMBDA {
-                            constexpr int e = decltype(E)::value, de = 8 * (e / 4) + (e & 3);
-                            if (full || kbase + de < ce->K) {
-                                // a copy first: a bit cast taken straight from a vector element
-                                // reads element 0 with this compiler
-                                const float v = acc[i * NMT + j][e];
-                                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), yrsrc,
-                                                                      voff, de * PQ4, policy);
-                            }
-                        });
-                    }
-                };
-                const bool whole = n0 + wave_n * TN + i * 32 + 32 <= ce->K;
-                if (ce->yl == 0) {
-                    if (whole)
-                        emit(std::true_type{}, std::true_type{});
-                    else
-                        emit(std::false_type{}, std::true_type{});
-                } else {
-                    if (whole)
-                        emit(std::true_type{}, std::false_type{});
-                    else
-                        emit(std::false_type{}, std::false_type{});
-                }
-            });
-        }
-    });
+    store_wave_tile<NNT, NMT>(ce, acc, m0 + wave_m * TM, n0 + wave_n * TN, lrow, lcol, mode == kAtomic);
     };  // run_segment
 
     // ---- which segments this workgroup runs ----------------------------------------------------
@@ -823,12 +855,21 @@ hipError_t launch_gather_form(IgemmArgs a, hipStream_t stream)
     return hipGetLastError();
 }
 
+// (wpk_wsplit.h)
+template <int BN, int WK, int PD>
+hipError_t launch_wsplit(const IgemmArgs &a, hipStream_t stream);
+
 template <int BM, int BN, int BK, int WM, int WN, int PD>
 hipError_t launch_igemm(const IgemmArgs &a, hipStream_t stream)
 {
-    if (a.xl == 2) return launch_gather_form<BM, BN, BK, WM, WN, PD, 1>(a, stream);
-    if (a.xl == 3) return launch_gather_form<BM, BN, BK, WM, WN, PD, 2>(a, stream);
-    return launch_gather_form<BM, BN, BK, WM, WN, PD, 0>(a, stream);
+    if constexpr (BM == kWaveSplitBm) {
+        static_assert(BK == 8, "the wave-split members work in octets");
+        return launch_wsplit<BN, WM * WN, 4 * PD>(a, stream);
+    } else {
+        if (a.xl == 2) return launch_gather_form<BM, BN, BK, WM, WN, PD, 1>(a, stream);
+        if (a.xl == 3) return launch_gather_form<BM, BN, BK, WM, WN, PD, 2>(a, stream);
+        return launch_gather_form<BM, BN, BK, WM, WN, PD, 0>(a, stream);
+    }
 }
 
 }  // namespace wpk

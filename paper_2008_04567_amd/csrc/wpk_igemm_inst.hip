@@ -1,6 +1,6 @@
 // Explicit instantiations of the tiled kernel family.  Compiled once per WPK_PART (0..7) so the
 // build can run the parts in parallel; each part emits the variants tagged with its number.
-#include "wpk_igemm.h"
+#include "wpk_wsplit.h"
 
 #ifndef WPK_PART
 #error "compile with -DWPK_PART=<0..7>"

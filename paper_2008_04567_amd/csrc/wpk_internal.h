@@ -19,7 +19,7 @@
 namespace wpk {
 
 // ---- gene value lists (the search sees index ranges into them) -------------------------------
-extern const int32_t kBmVals[3];     // 64, 128, 256
+extern const int32_t kBmVals[4];     // 32 (the wave-split members), 64, 128, 256
 extern const int32_t kBnVals[3];     // 32, 64, 128
 extern const int32_t kBkVals[3];     // 8, 16, 32
 extern const int32_t kWmVals[3];     // 1, 2, 4
@@ -44,6 +44,9 @@ static const int kMaxFilterRows = 16;
 static const int kMaxFilterCols = 15;
 static const int kPadTapBit = 31;
 static const int kNumXcd = 8;
+// Members with this pixel tile are the wave-split form (wpk_wsplit.h): their wm x wn waves cut the
+// reduction between them, bk is the octet they work in, and `stages` counts four octets in flight each.
+static const int kWaveSplitBm = 32;
 // LDS per workgroup: two stages of (BM + BN) columns of BK + 4 floats; two workgroups of the
 // largest tile still fit the 160 KB of a compute unit.
 static const int kMaxLdsBytes = 80 * 1024;
@@ -184,6 +187,9 @@ void set_device_name(const std::string &name);
 std::string device_name();
 bool legal_for(const Problem &pr, const wpk_conv_config &cfg);
 void default_config(const Problem &pr, int compute_units, wpk_conv_config *out);
+// Whether the wave-split members can run pr at all and its 32 x 32 output blocks times its octets of
+// reduction rows stay within the bound (the work is then small enough for them to be worth timing).
+bool wave_split_candidate(const Problem &pr, int64_t max_block_octets);
 
 }  // namespace wpk
 #endif

@@ -124,10 +124,11 @@ def test_error_codes():
 
 def test_config_encoding_roundtrip_and_constraint_check():
     lo, hi = B.config_gene_ranges()
-    assert lo == [0] * 10 and hi == [2, 2, 2, 2, 2, 17, 1, 4, 2, 1]
+    assert lo == [0] * 10 and hi == [3, 2, 2, 2, 2, 17, 1, 4, 2, 1]
     d = B.make_desc(W.config3()[1])
     legal = B.legal_configs(d)
-    assert 3000 < len(legal) < 15000
+    assert 3000 < len(legal) < 20000
+    assert any(c.bm == 32 for c in legal)
     ids = set()
     for c in legal:
         cid = B.config_id(c)
@@ -136,8 +137,12 @@ def test_config_encoding_roundtrip_and_constraint_check():
         assert B.config_kernel_name(c) == "wpk_igemm_%dx%dx%d_%dx%d_p%d" % (c.bm, c.bn, c.bk, c.wm, c.wn, c.stages)
         # the constraints the header states
         assert 64 * c.wm * c.wn <= 1024
-        assert 2 * (c.bk + 4) * (c.bm + c.bn) * 4 <= 80 * 1024
-        assert (c.bm // c.wm) % 32 == 0 and (c.bn // c.wn) % 32 == 0
+        if c.bm == 32:      # wave-split members: the waves cut the reduction, every wave holds the whole tile
+            assert c.bk == 8 and c.persist == 0 and c.bn in (32, 64) and c.wm * c.wn in (1, 2, 4, 8)
+            assert (c.wm * c.wn - 1) * 32 * c.bn * 4 <= 80 * 1024
+        else:
+            assert 2 * (c.bk + 4) * (c.bm + c.bn) * 4 <= 80 * 1024
+            assert (c.bm // c.wm) % 32 == 0 and (c.bn // c.wn) % 32 == 0
         ids.add(cid)
     assert len(ids) == len(legal)
     assert not B.config_legal(d, B.make_config(128, 64, 16, 1, 1))          # not built

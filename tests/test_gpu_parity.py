@@ -121,6 +121,53 @@ def test_tiles_numbered_along_the_pixels_first():
                         repr(c) + " fused")
 
 
+def test_wave_split_members_every_variant_and_way_of_meeting():
+    """The members whose waves cut the reduction between them (bm = 32): every built combination of
+    channels per tile, waves and fetch depth, alone and with the reduction cut between workgroups as
+    well (partial tiles through the workspace and through atomics, slices that do not divide the
+    octets, more waves than octets), on ragged pixels with a channel count that is no multiple of 32,
+    on a pointwise layer and on a strided one; every case twice, so the second launch finds the
+    arrival counters as the first left them.  Then all four layout codes, plain and with bias,
+    residual and rectifier fused."""
+    la = W.layer("ws.ragged", 2, 32, (13, 11), 40, 3, 1, 1, x_dist="u11", seed=111)
+    lb = W.layer("ws.pointwise", 3, 64, (9, 10), 96, 1, 1, 0, x_dist="u11", seed=112)
+    lc = W.layer("ws.strided", 2, 32, (15, 14), 64, 3, 2, 1, x_dist="u11", seed=113)
+    ld = W.layer("ws.dilated", 1, 32, (12, 12), 33, 3, 1, 2, dil=2, x_dist="u11", seed=114)
+    seen = set()
+    for l in (la, lb, lc, ld):
+        desc = B.make_desc(l)
+        x, w = W.make_inputs(l)
+        y_ref, d_ref = PT.oracle_full(l, x, w)
+        for bn in (32, 64):
+            for wm, wn in ((1, 1), (2, 1), (4, 1), (4, 2)):
+                for stages in (1, 2, 3):
+                    for split, reduce in ((1, 0), (2, 0), (3, 1), (5, 0), (7, 1)):
+                        c = B.ConvConfig(32, bn, 8, wm, wn, split, 1 if split in (2, 7) else 0, 0, stages, reduce)
+                        if not B.config_legal(desc, c):
+                            assert split > l["c"] * l["r"] * l["s"] // 8, c   # only: more slices than octets
+                            continue
+                        seen.add((bn, wm, wn, stages))
+                        print(l["name"], c, flush=True)
+                        for again in range(2 if split > 1 else 1):
+                            y = PT.run_gpu(l, x, w, cfg=c)
+                            PT.assert_close(y, y_ref, d_ref, "%s %r launch %d" % (l["name"], c, again))
+    assert len(seen) == 24
+    assert not B.config_legal(B.make_desc(RAGGED), B.ConvConfig(32, 32, 8, 4, 1, 1, 0, 0, 1, 0))   # C = 20
+    assert not B.config_legal(B.make_desc(la), B.ConvConfig(32, 32, 8, 4, 1, 1, 1, 1, 1, 0))       # persistent
+    assert not B.config_legal(B.make_desc(la), B.ConvConfig(32, 32, 16, 4, 1, 1, 0, 0, 1, 0))      # not in octets
+    rng = np.random.default_rng(3)
+    for l in (la, lb):
+        P, Q = B.conv_out_shape(B.make_desc(l))
+        bias = rng.uniform(-0.5, 0.5, l["k"]).astype(np.float32)
+        res = rng.uniform(-1, 1, (l["n"], l["k"], P, Q)).astype(np.float32)
+        for layout in (0, 1, 2, 3):
+            for c in (B.ConvConfig(32, 32, 8, 4, 1, 1, 0, 0, 2, 0), B.ConvConfig(32, 64, 8, 2, 1, 3, 1, 0, 1, 0),
+                      B.ConvConfig(32, 64, 8, 4, 2, 2, 0, 0, 3, 1)):
+                print(l["name"], "layout", layout, c, flush=True)
+                PT.check_layout(l, layout, cfg=c)
+                PT.check_layout(l, layout, cfg=c, bias=bias, residual=res, relu=True)
+
+
 def test_split_k_and_remap_settings():
     desc = B.make_desc(RAGGED)
     x, w = W.make_inputs(RAGGED)
