@@ -492,7 +492,8 @@ def main():
                     "bytes_per_launch": total_bytes / n}
     dom = int(np.argmin([r["tflops"] / FP32_MFMA_PEAK_TFLOPS if r["bound"] == "mfma"
                          else r["gbs_algorithmic"] / HBM_PEAK_GBS for r in rows]))
-    roofline.update({"kernel": "wpk::igemm_kernel<...> (tiled implicit-GEMM family; all %d launches of a pass: %s)"
+    roofline.update({"kernel": "wpk::igemm_kernel<...> / wpk::wsplit_kernel<...> (implicit-GEMM family, tiled members "
+                               "and wave-split ones, named wpk_igemm_32x...; all %d launches of a pass: %s)"
                                % (n, ", ".join(sorted(set(r["kernel"] for r in rows)))),
                      "launches_per_pass": n, "avg_us": round(region_us / n, 2),
                      "how": "algorithmic work of a pass / duration of the %d timed passes between two events on the "

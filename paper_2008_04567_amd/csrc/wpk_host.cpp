@@ -246,13 +246,16 @@ static bool wave_split_default(const Problem &pr, int compute_units, wpk_conv_co
 {
     if (!wave_split_candidate(pr, 20000)) return false;
     const int64_t blocks = ((pr.M + 31) / 32) * ((pr.d.k + 31) / 32), octets = pr.CRS / 8;
-    const int wk = 4;
+    // as many waves per tile (four at most) as keep the launch within one wave per SIMD and every wave
+    // at four octets or more
+    int wk = 4;
+    while (wk > 1 && (blocks * wk > 4 * (int64_t)compute_units || octets / wk < 4)) wk /= 2;
     int64_t want = std::max<int64_t>(1, 4 * (int64_t)compute_units / (blocks * wk));
-    while (want > 1 && octets / (wk * want) < 12) --want;
+    while (want > 1 && octets / (wk * want) < 8) --want;
     wpk_conv_config c = {kWaveSplitBm, 32, 8, wk, 1, 1, 1, 0, 1, 0};
     for (int i = 0; i < kGeneCounts[5]; ++i)
         if (kSplitVals[i] <= want) c.split_k = kSplitVals[i];
-    c.reduce = c.split_k >= 8 ? 1 : 0;
+    c.reduce = c.split_k >= 4 ? 1 : 0;
     if (!legal_for(pr, c)) return false;
     *out = c;
     return true;
@@ -261,9 +264,9 @@ void default_config(const Problem &pr, int compute_units, wpk_conv_config *out)
 {
     if (compute_units <= 0) compute_units = 256;
     // A launch with a few microseconds of arithmetic at most (single images, late layers): the
-    // wave-split members, four waves per 32 x 32 tile, the reduction cut further between workgroups
-    // until about one wave per SIMD is busy, but not into runs of fewer than twelve octets; many
-    // slices add up with atomics.  (Measured on the single-image ResNet-50 layers: 4.3-9.8 us where
+    // wave-split members, up to four waves per 32 x 32 tile, the reduction cut further between
+    // workgroups until about one wave per SIMD is busy, but not into runs of fewer than eight octets;
+    // four slices or more add up with atomics.  (Measured on the single-image ResNet-50 layers: 4.3-9.8 us where
     // the tiled members' best is 4.9-10.6.)
     if (wave_split_default(pr, compute_units, out)) return;
     wpk_conv_config c = {64, pr.d.k <= 32 ? 32 : 64, pr.CRS >= 64 ? 32 : pr.CRS >= 32 ? 16 : 8, 2,
