@@ -14,9 +14,9 @@
 // the tiled members need a reduction cut five ways across workgroups, these need none, or a
 // shorter one.
 //
-// Operands.  Reduction rows are ordered (r, s, c) (the tap-major forms: C a multiple of 8 here
-// because of the K-steps the tiled members of the same plan may use, see Problem::tapmajor), and
-// the unit of work is an octet of eight rows: eight consecutive channels of one filter tap.  In the
+// Operands.  Reduction rows are ordered (r, s, c) (the tap-major forms of the family: C a multiple
+// of 32, see Problem::tapmajor and Problem::xquad), and the unit of work is an octet of eight
+// rows: eight consecutive channels of one filter tap.  In the
 // octet's four MFMAs (v_mfma_f32_32x32x2_f32) the low half-wave supplies rows 0..3 and the high
 // half-wave rows 4..7, as in the tiled members.  So per octet a lane loads
 //   weights: one 16-byte quad per 32-channel block -- packed [row/4][channel][4] is exactly that;

@@ -133,8 +133,9 @@ def test_wave_split_members_every_variant_and_way_of_meeting():
     lb = W.layer("ws.pointwise", 3, 64, (9, 10), 96, 1, 1, 0, x_dist="u11", seed=112)
     lc = W.layer("ws.strided", 2, 32, (15, 14), 64, 3, 2, 1, x_dist="u11", seed=113)
     ld = W.layer("ws.dilated", 1, 32, (12, 12), 33, 3, 1, 2, dil=2, x_dist="u11", seed=114)
+    le = W.layer("ws.49taps", 1, 32, (20, 17), 32, 7, 2, 3, x_dist="u11", seed=115)     # more taps than table padding
     seen = set()
-    for l in (la, lb, lc, ld):
+    for l in (la, lb, lc, ld, le):
         desc = B.make_desc(l)
         x, w = W.make_inputs(l)
         y_ref, d_ref = PT.oracle_full(l, x, w)

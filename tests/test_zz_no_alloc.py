@@ -50,8 +50,13 @@ def test_no_alloc_entry_point_matches_the_allocating_one():
     small = W.layer("na.small", 1, 12, (9, 11), 20, (3, 2), (2, 1), (1, 0), x_dist="u11", seed=402)
     # third: a persistent launch whose left-over tiles meet in the workspace, then atomics
     third = W.layer("na.third", 3, 16, (20, 20), 32, 3, 1, 1, x_dist="u11", seed=403)
+    # fifth: a wave-split member (tap-major input), slices meeting in the workspace, then the default, which
+    # for so small a problem is a wave-split member too
+    fifth = W.layer("na.fifth", 1, 32, (14, 13), 48, 3, 1, 1, x_dist="u11", seed=404)
     cases = [(big, cfg), (small, None), (third, B.make_config(64, 32, 16, 2, 1, persist=1)),
-             (big, B.make_config(64, 64, 16, 2, 2, split_k=4, reduce=1))]
+             (big, B.make_config(64, 64, 16, 2, 2, split_k=4, reduce=1)),
+             (fifth, B.make_config(32, 32, 8, 4, 1, split_k=3, stages=1)), (fifth, None)]
+    assert B.config_default(B.make_desc(fifth)).bm == 32
     for layer, c in cases:
         mine, theirs, y_ref, d_ref = _both(layer, c)
         # the two entry points run the same kernels; split sums come in arrival order, so they are
