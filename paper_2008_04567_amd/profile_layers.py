@@ -8,8 +8,8 @@ configurations a search stored there (``--tune`` searches
 the missing ones first and saves them: do that in a run of its own, outside the profiler); without
 it under the library's defaults.  The manifest lists the convolution launches in order -- layer,
 configuration, kernel name, grid size, algorithmic bytes and FLOPs -- so that a per-dispatch
-counter file can be read layer by layer: the n-th dispatch of a kernel of the tiled family belongs
-to the n-th manifest entry.  ``--calibrate-copy`` appends three device copies of 256 MiB, whose
+counter file can be read layer by layer: the n-th dispatch of a convolution kernel (``igemm_kernel``,
+``wsplit_kernel`` or the direct kernel) belongs to the n-th manifest entry.  ``--calibrate-copy`` appends three device copies of 256 MiB, whose
 byte counters give the scale of FETCH_SIZE / WRITE_SIZE.
 """
 import argparse
