@@ -519,6 +519,7 @@ static int run_config(const Problem &pr, const wpk_conv_config &cfg, const int32
     a.div_q = make_fastdiv((uint32_t)a.Q);
     a.div_tiles_n = make_fastdiv((uint32_t)a.tiles_n);
     a.div_tiles_m = make_fastdiv((uint32_t)a.tiles_m);
+    a.div_s = make_fastdiv((uint32_t)d.s);
     // weights the larger operand: tiles that share them are made neighbours (see IgemmArgs::mfast)
     a.mfast = pr.w_elems > pr.x_elems ? 1 : 0;
     a.div_tiles = make_fastdiv((uint32_t)a.tiles);

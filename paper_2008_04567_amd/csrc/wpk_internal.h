@@ -155,6 +155,7 @@ struct IgemmArgs {
                         // of x); 1: tile = tile_n * tiles_m + tile_m (neighbours share weights) -- whichever operand is
                         // the larger, since with XCD-contiguous ranges the other one is what every XCD fetches whole
     FastDiv div_tiles_m;  // by tiles_m
+    FastDiv div_s;        // by S (the wave-split members find their first filter tap with it)
     int32_t xl;         // 0: x is [N][C][H][W]; 1: channels-last, gathered row by row; 2: channels-last,
                         // gathered as 16-byte channel quads (reduction rows ordered (r, s, c)); 3: [N][C][H][W]
                         // with the reduction ordered (r, s, c), one filter tap per step

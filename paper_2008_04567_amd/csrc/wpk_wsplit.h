@@ -1,8 +1,9 @@
 // The wave-split members of the convolution kernel family for gfx950: for launches whose
 // arithmetic is a few microseconds at most (single images, late layers of few pixels).
 //
-// Same GEMM view, same packed weights, same tap table and same output code as the tiled members
-// (wpk_igemm.h).  What differs is who shares what.  A tiled workgroup stages its operands through
+// Same GEMM view, same packed weights and same output code as the tiled members (wpk_igemm.h);
+// the filter taps are followed by arithmetic instead of being read from the tap table.  What
+// differs is who shares what.  A tiled workgroup stages its operands through
 // LDS so that every wave reuses them, and it needs a long reduction per workgroup to repay the
 // staging, the barriers and -- when the reduction has to be cut between workgroups to fill the
 // device -- the meeting of the partial tiles in memory, several dependent memory round trips at
@@ -74,15 +75,21 @@ __global__ void __launch_bounds__(64 * WK) wsplit_kernel(const IgemmArgs a)
         (void *)((const char *)a.x - a.x_bias), 0, (int)(a.x_bytes + a.x_bias), 0x00020000);
     const __amdgpu_buffer_rsrc_t wrsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.wp, 0, (int)a.w_bytes, 0x00020000);
-    const tap_ptr taps = (tap_ptr)(unsigned long long)a.ktab;
 
-    // ---- the loader's place in the reduction: the next octet to fetch, its tap number and first
-    //      channel, and the tap's table entry (byte offset, mask bit numbers) --------------------------
+    // ---- the loader's place in the reduction: the next octet to fetch, its first channel, and its
+    //      filter tap (r, s) with the tap's byte offset in x.  Kept by arithmetic on the scalar unit
+    //      (a step along the filter row, or to the start of the next one), not read from the tap table:
+    //      a table entry costs a memory round trip before the first fetch can go out, which a launch
+    //      of a few microseconds notices. ---------------------------------------------------------------
+    const int px4 = QUAD ? a.C * 4 : 4;  // bytes between neighbouring pixels of x
+    const int tap_step_s = c->dil_w * px4;
+    const int tap_step_r = (c->dil_h * a.W - (a.S - 1) * c->dil_w) * px4;
     int ld_o = obeg;
-    int ld_tap = min(fdiv(obeg * 8, WPK_COLD_DIV(c, div_tap)), a.RS - 1);  // by C
-    int ld_c0 = obeg * 8 - ld_tap * a.C;
-    int tap_off = taps[2 * ld_tap];
-    int tap_rs = taps[2 * ld_tap + 1];
+    const int tap0 = fdiv(obeg * 8, WPK_COLD_DIV(c, div_tap));  // by C
+    int ld_c0 = obeg * 8 - tap0 * a.C;
+    int tap_r = fdiv(tap0, WPK_COLD_DIV(c, div_s));
+    int tap_s = tap0 - tap_r * a.S;
+    int tap_off = (tap_r * c->dil_h * a.W + tap_s * c->dil_w) * px4;
     // weights: the lane's quad of the octet's first block row, its channel
     const int wvoff = (lrow * a.Kpad + n0 + lcol) * 16;
     const int woct_bytes = 2 * a.Kpad * 16;  // one octet further
@@ -102,8 +109,8 @@ __global__ void __launch_bounds__(64 * WK) wsplit_kernel(const IgemmArgs a)
     auto issue = [&](auto SET) WPK_LAMBDA {
         constexpr int set = decltype(SET)::value;
         const int dead = ld_o < oend ? 0 : -1;
-        const int xvb = xvoff | __builtin_amdgcn_sbfe((int)xinv, tap_rs & 0xff, 1) |
-                        __builtin_amdgcn_sbfe((int)xinv, tap_rs >> 8, 1) | dead;  // offset, or all ones
+        const int xvb = xvoff | __builtin_amdgcn_sbfe((int)xinv, tap_r, 1) |
+                        __builtin_amdgcn_sbfe((int)xinv, 16 + tap_s, 1) | dead;  // offset, or all ones
         if constexpr (QUAD) {
             v4f v = __builtin_bit_cast(
                 v4f, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, xvb, tap_off + ld_c0 * 4, 0));
@@ -124,14 +131,15 @@ __global__ void __launch_bounds__(64 * WK) wsplit_kernel(const IgemmArgs a)
             wr[set * NNT + i] = __builtin_bit_cast(
                 v4f, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wv, ld_o * woct_bytes + i * 32 * 16, 0));
         });
-        // (no branch at the change of tap: the entry is read again for every octet, a scalar load that
-        // hits and has the next octet's MFMAs to arrive in; past the last tap nothing more is fetched)
+        // (no branch at the change of tap: selects on the scalar unit; past the last tap the place keeps
+        // moving, but nothing more is fetched)
         ld_o += 1;
         const bool next_tap = ld_c0 + 8 >= a.C;
+        const bool next_row = next_tap && tap_s + 1 == a.S;
         ld_c0 = next_tap ? 0 : ld_c0 + 8;
-        ld_tap = next_tap ? min(ld_tap + 1, a.RS - 1) : ld_tap;
-        tap_off = taps[2 * ld_tap];
-        tap_rs = taps[2 * ld_tap + 1];
+        tap_off += next_row ? tap_step_r : next_tap ? tap_step_s : 0;
+        tap_s = next_row ? 0 : next_tap ? tap_s + 1 : tap_s;
+        tap_r += next_row ? 1 : 0;
     };
 
     v16f acc[NNT];
