@@ -134,7 +134,10 @@ __host__ __device__ constexpr int lds_pitch(int bk) { return bk + 4; }
 // negative); inv: bit r set = filter row r is outside the image for this pixel, bit 16+s = column s;
 // bit 31 is always set and is what the table's padding rows point at.  A pixel past the last one
 // has every bit set.
-__device__ __forceinline__ void pixel_window(const cold_ptr c, const int m, int &voff, unsigned &inv_out)
+// (ARGS: a pointer to the arguments -- cold_ptr where they are to be read at the place of use, a plain
+// pointer to the by-value kernel argument where the compiler may keep them in scalar registers)
+template <class ARGS>
+__device__ __forceinline__ void pixel_window(const ARGS c, const int m, int &voff, unsigned &inv_out)
 {
     voff = 0;
     inv_out = 0xffffffffu;
@@ -174,8 +177,8 @@ __device__ __forceinline__ void pixel_window(const cold_ptr c, const int m, int 
 
 // ---- what leaves a wave: its NNT x NMT accumulator blocks, whose first pixel is mbase and first
 //      channel nbase, go to y -- plain stores with the fused epilogue applied, or fp32 atomics ----
-template <int NNT, int NMT>
-__device__ __forceinline__ void store_wave_tile(const cold_ptr ce, const v16f (&acc)[NNT * NMT], const int mbase,
+template <int NNT, int NMT, class ARGS>
+__device__ __forceinline__ void store_wave_tile(const ARGS ce, const v16f (&acc)[NNT * NMT], const int mbase,
                                                 const int nbase, const int lrow, const int lcol, const bool atomic)
 {
     // the host applies the epilogue itself after a launch that accumulates with atomics

@@ -51,7 +51,10 @@ __global__ void __launch_bounds__(64 * WK) wsplit_kernel(const IgemmArgs a)
     const int lrow = lane >> 5, lcol = lane & 31;
 
     // ---- which tile, which slice of the reduction -------------------------------------------------
-    const cold_ptr c = cold_args();
+    // (the arguments are used straight from the by-value kernel argument: this kernel has scalar
+    // registers to spare, and every argument read at its place of use would be one more wait on the
+    // scalar cache in a set-up that is a sixth of a short launch)
+    const IgemmArgs *const c = &a;
     const int g = blockIdx.x;
     const int gr = a.remap ? xcd_remap(g, (int)gridDim.x) : g;
     const int slice = fdiv(gr, WPK_COLD_DIV(c, div_tiles));
@@ -203,7 +206,7 @@ __global__ void __launch_bounds__(64 * WK) wsplit_kernel(const IgemmArgs a)
     // ---- a reduction cut between workgroups: the slices of a tile meet through the workspace (each
     //      stores its partial tile to its slot and counts itself in; whoever comes last adds up the
     //      others and stores y), or, without one, through atomics into y, which the host zeroed ------
-    const cold_ptr ce = cold_args();
+    const IgemmArgs *const ce = &a;
     bool atomic = false;
     if (ce->split_k > 1) {
         if (!ce->ws) {
